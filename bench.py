@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the GatedFWA hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: gate prefix scan,
+fused forward, and backward (row-dot, dK/dV, dQ, gate-gradient scan).  The default workload is the
+one the target is stated on: B=1, H=32, N=16384, d=128, w=1024, bf16.  Prints ONE JSON line.
+
+metric/value: effective TFLOP/s on in-window FLOPs of forward + backward, nominal count
+(4 + 10) * B*H*N*w*d, inputs resident in HBM.  Forward-only and backward-only figures and their
+fraction of the bf16 MFMA peak are reported in "detail".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="long_bwd")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=8)
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no inter-GPU part); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import gfwa_inputs as gi
+    import paper_2512_07782_amd as g
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    g.load_library()
+    dev = "cuda:0"
+    wl = gi.WORKLOADS[args.workload]
+    ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha", "dO")} if wl.backward else gi.make_inputs(wl)
+    bf = wl.dtype == "bf16"
+    to = lambda x, b: (torch.from_numpy(x).to(dev).to(torch.bfloat16) if b else torch.from_numpy(x).to(dev))
+    Q, K, V = (to(ins[k], bf) for k in ("Q", "K", "V"))
+    dO = to(ins["dO"], bf) if wl.backward else None
+    alpha = to(ins["alpha"], False)
+    B, H, N, d, w = wl.B, wl.H, wl.N, wl.d, wl.w
+
+    c = torch.empty_like(alpha)
+    O = torch.empty_like(Q)
+    L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    if wl.backward:
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+        dalpha = torch.empty_like(alpha)
+        ws = torch.empty(g.gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=dev)
+
+    def step():
+        g.gfwa_gate_prefix(alpha, c)
+        g.gfwa_forward(Q, K, V, c, w, wl.scale, O=O, L=L)
+        if wl.backward:
+            g.gfwa_backward(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ, dK=dK, dV=dV, dalpha=dalpha)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    g.gfwa_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    g.gfwa_profile_enable(False)
+    prof = g.gfwa_profile_read()
+    ms_per_step = elapsed / args.steps * 1e3
+
+    f_fwd = wl.flops_fwd_nominal()
+    f_bwd = wl.flops_bwd_nominal() if wl.backward else 0.0
+    bhn = B * H * N
+    # algorithmic work per launch of each kernel
+    algo = {
+        "gate_prefix_scan": ("hbm", 8.0 * bhn),
+        "forward": ("mfma", f_fwd),
+        "bwd_rowdot": ("hbm", bhn * (4.0 * d + 4.0)),
+        "bwd_dkv": ("mfma", 8.0 * bhn * w * d),     # S, dP, dV, dK products
+        "bwd_dq": ("mfma", 2.0 * bhn * w * d),      # the dQ product; its S and dP are recomputation
+        "gate_grad_scan": ("hbm", 12.0 * bhn),
+    }
+    kernels = {}
+    for name, (tot, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        avg_ms = tot / cnt
+        bound, work = algo[name]
+        if bound == "mfma":
+            ach, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        kernels[name] = {"avg_ms": round(avg_ms, 5), "launches": cnt, "bound": bound, "achieved": round(ach, 2),
+                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            traffic = json.load(open(args.traffic_json)).get(args.workload, {}).get(dominant)
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
+                "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
+                "frac": kernels[dominant]["frac"], "traffic": traffic}
+
+    fwd_ms = kernels["forward"]["avg_ms"]
+    detail = {"fwd_ms": fwd_ms, "fwd_tflops_nominal": round(f_fwd / fwd_ms / 1e9, 2),
+              "fwd_tflops_exact": round(wl.flops_fwd_exact() / fwd_ms / 1e9, 2),
+              "fwd_frac_bf16_peak": round(f_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    if wl.backward:
+        bwd_ms = sum(kernels[k]["avg_ms"] for k in ("bwd_rowdot", "bwd_dkv", "bwd_dq", "gate_grad_scan"))
+        detail.update({"bwd_ms": round(bwd_ms, 5), "bwd_tflops_nominal": round(f_bwd / bwd_ms / 1e9, 2),
+                       "bwd_frac_bf16_peak": round(f_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nh = min(args.cpu_heads, B * H)
+        heads = list(range(nh))
+        sel = lambda x, tr: oracle.select_heads(x, heads, tr)
+        t0 = time.perf_counter()
+        cs = oracle.gate_prefix(sel(ins["alpha"], 1))
+        if wl.backward:
+            oracle.backward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, sel(ins["dO"], 2), w, wl.scale)
+        else:
+            oracle.forward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, w, wl.scale)
+        dt_cpu = time.perf_counter() - t0
+        frac = nh / (B * H)
+        cpu = {"value": round((f_fwd + f_bwd) * frac / dt_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.threads(),
+               "kind": "oracle", "sample": f"{nh} of {B*H} (b,h) heads of the same workload, forward"
+               + ("+backward" if wl.backward else "") + f", {dt_cpu:.1f} s"}
+
+    out = {
+        "metric": "GatedFWA fwd+bwd effective TFLOP/s (in-window FLOPs, nominal) on 1 GPU",
+        "value": round((f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={B} H={H} N={N} d={d} w={w} {wl.dtype}, gate prefix + forward"
+                   + (" + backward" if wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS},
+        "roofline": roofline, "cpu_baseline": cpu, "detail": detail, "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,119 @@
+/*
+ * gfwa.h -- C ABI of libgfwa: GatedFWA (memory-gated sliding-window softmax attention)
+ * for AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library allocates no
+ *    persistent device memory and never frees anything.  Inputs are never written; outputs
+ *    are fully overwritten (no accumulate-into semantics).
+ *  - Dense row-major layouts: Q, K, V, O, dO, dQ, dK, dV are [B, H, N, d] with d fastest;
+ *    alpha, c, L, dalpha are [B, H, N] with N fastest.  Matrix pointers must be 16-byte
+ *    aligned, vector pointers 4-byte aligned.
+ *  - `stream` is the caller's HIP stream (NULL = the default stream).  Work is enqueued and
+ *    the call returns without synchronising.
+ *  - Positions are 0-indexed.  Query t attends to keys i with  t - w < i <= t  and  i >= 0.
+ *    w >= 1; w >= N is legal and means plain causal attention with the gate bias.
+ *  - Return value: GFWA_OK or a negative gfwa_status_t.  On error nothing is launched and
+ *    nothing is written.  alpha < 0 or non-finite inputs are not checked: results undefined.
+ */
+#ifndef GFWA_H
+#define GFWA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t *gfwa_stream_t;
+
+typedef enum {
+    GFWA_BF16 = 0, /* Q,K,V,O,dO,dQ,dK,dV stored as bfloat16; products on bf16 MFMA, fp32 accumulate */
+    GFWA_F32 = 1   /* stored as float; all arithmetic fp32 */
+} gfwa_dtype_t;
+
+typedef enum {
+    GFWA_OK = 0,
+    GFWA_ERR_NULL = -1,        /* a required pointer is NULL */
+    GFWA_ERR_DIM = -2,         /* B, H, N or d <= 0, w < 1, or B*H*N*d exceeds the index range */
+    GFWA_ERR_UNSUPPORTED = -3, /* d not in {64, 128} or unknown dtype */
+    GFWA_ERR_ALIGN = -4,       /* pointer alignment */
+    GFWA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than gfwa_backward_workspace_bytes() */
+    GFWA_ERR_HIP = -6          /* the HIP runtime refused a launch; see gfwa_strerror */
+} gfwa_status_t;
+
+/*
+ * Gate preprocessing, scan part (paper Sec. 3.2, definition of u_t; Alg. 1, the cumulative-sum
+ * and carry steps; Sec. 3.3 "Gate Preprocessing via Fused Tiled Scan").
+ *
+ *   c[b,h,t] = sum_{q <= t} alpha[b,h,q]        (inclusive; c = -u in the paper's notation)
+ *
+ * alpha: [B,H,N] fp32, expected >= 0.   c: [B,H,N] fp32 out.  fp32 accumulation.
+ */
+int gfwa_gate_prefix(const float *alpha, float *c, int B, int H, int N, gfwa_stream_t stream);
+
+/*
+ * Fused forward (paper Sec. 3.2, the gated score; Alg. 2).  For every (b,h) and query t:
+ *
+ *   S_ti = scale * <q_t, k_i> + (c_i - c_t)     for  max(0, t-w+1) <= i <= t
+ *   O_t  = sum_i softmax_i(S_ti) v_i
+ *   L_t  = log sum_i exp(S_ti)                  (natural log; what Alg. 2 returns as m + log l)
+ *
+ * The N x N matrix is never formed; key tiles wholly outside the band are skipped.
+ * `scale` multiplies q.k only (1/sqrt(d) in the paper's workloads), never the bias.
+ * Q,K,V: [B,H,N,d] of dtype `dt`;  c: [B,H,N] fp32 (from gfwa_gate_prefix);
+ * O: [B,H,N,d] of dtype `dt`, out;  L: [B,H,N] fp32, out.   d in {64, 128}.
+ */
+int gfwa_forward(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, const float *c,
+                 void *O, float *L, int B, int H, int N, int d, int w, float scale,
+                 gfwa_stream_t stream);
+
+/* Bytes of device scratch gfwa_backward needs for these sizes (0 on invalid sizes). */
+size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w);
+
+/*
+ * Backward (paper App. E.2, Alg. 3, plus the chain-rule factor `scale` on dQ and dK and the
+ * reverse scan of Sec. 3.3 "gradients into U flow through the same streamed scan").
+ * With P_ti = exp(S_ti - L_t) recomputed from the saved L:
+ *
+ *   D_t   = <dO_t, O_t>                         dP_ti = <dO_t, v_i>
+ *   dS_ti = P_ti (dP_ti - D_t)
+ *   dV_i  = sum_t P_ti dO_t                     dK_i = scale * sum_t dS_ti q_t
+ *   dQ_t  = scale * sum_i dS_ti k_i
+ *   dc_p  = sum_t dS_tp - sum_i dS_pi           dalpha_q = sum_{p >= q} dc_p
+ *
+ * Inputs: Q,K,V,O,dO [B,H,N,d] of dtype `dt` (O and L as written by gfwa_forward), c, L [B,H,N] fp32.
+ * Outputs: dQ,dK,dV [B,H,N,d] of dtype `dt`; dalpha [B,H,N] fp32.
+ * workspace: device scratch of at least gfwa_backward_workspace_bytes(...) bytes, 16-byte
+ * aligned, contents undefined before and after the call.
+ */
+int gfwa_backward(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, const void *O,
+                  const void *dO, const float *c, const float *L, void *dQ, void *dK, void *dV,
+                  float *dalpha, void *workspace, size_t workspace_bytes, int B, int H, int N,
+                  int d, int w, float scale, gfwa_stream_t stream);
+
+/* Static, human-readable text for a status code (for GFWA_ERR_HIP: the last HIP error text). */
+const char *gfwa_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gfwa_version(void);
+
+/*
+ * Instrumentation (not part of the method): per-kernel timing with HIP events recorded on the
+ * caller's stream around every kernel the library launches.  gfwa_profile_enable(1) clears the
+ * records and starts recording (at most 8192 launches are kept), gfwa_profile_enable(0) stops.
+ * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 6), the
+ * summed duration in milliseconds and the number of launches; n must be >= 6.  Kernel ids:
+ * 0 gate prefix scan, 1 forward, 2 backward row-dot (D), 3 backward dK/dV, 4 backward dQ,
+ * 5 gate-gradient reverse scan; gfwa_profile_kernel_name gives the same as text.
+ * Not thread-safe; host memory only.
+ */
+int gfwa_profile_enable(int on);
+int gfwa_profile_read(float *total_ms, int *launches, int n);
+const char *gfwa_profile_kernel_name(int k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GFWA_H */

@@ -1,0 +1,20 @@
+"""GatedFWA (memory-gated sliding-window softmax attention) for AMD MI355X.
+
+Thin Python binding over the C ABI of `libgfwa.so` (see `include/gfwa.h`).  The binding only
+marshals arguments: every step of the path runs in the HIP kernels.  PyTorch is used for device
+memory and streams.
+"""
+from .binding import (  # noqa: F401
+    GfwaError,
+    gfwa_backward,
+    gfwa_backward_workspace_bytes,
+    gfwa_forward,
+    gfwa_gate_prefix,
+    gfwa_profile_enable,
+    gfwa_profile_kernel_name,
+    gfwa_profile_read,
+    gfwa_strerror,
+    gfwa_version,
+    lib_path,
+    load_library,
+)

@@ -1,0 +1,193 @@
+"""ctypes binding with the same names as the C ABI (include/gfwa.h).
+
+Each function takes torch tensors living on the GPU, checks shapes/dtypes/contiguity on the
+host, and passes raw device pointers and the current HIP stream to the library.  There is no
+fallback: if `libgfwa.so` has not been built the import of the library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgfwa.so")
+_lib: Optional[ctypes.CDLL] = None
+
+GFWA_BF16, GFWA_F32 = 0, 1
+
+EXPORTS = ("gfwa_gate_prefix", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
+           "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
+           "gfwa_profile_kernel_name")
+N_KERNELS = 6
+
+
+class GfwaError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libgfwa error {code}: {text}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libgfwa.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, fp, i, f = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.gfwa_gate_prefix.argtypes = [fp, fp, i, i, i, vp]
+    lib.gfwa_gate_prefix.restype = i
+    lib.gfwa_forward.argtypes = [i, vp, vp, vp, fp, vp, fp, i, i, i, i, i, f, vp]
+    lib.gfwa_forward.restype = i
+    lib.gfwa_backward_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.gfwa_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.gfwa_backward.argtypes = [i, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, ctypes.c_size_t,
+                                  i, i, i, i, i, f, vp]
+    lib.gfwa_backward.restype = i
+    lib.gfwa_strerror.argtypes = [i]
+    lib.gfwa_strerror.restype = ctypes.c_char_p
+    lib.gfwa_version.argtypes = []
+    lib.gfwa_version.restype = i
+    lib.gfwa_profile_enable.argtypes = [i]
+    lib.gfwa_profile_enable.restype = i
+    lib.gfwa_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i]
+    lib.gfwa_profile_read.restype = i
+    lib.gfwa_profile_kernel_name.argtypes = [i]
+    lib.gfwa_profile_kernel_name.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def gfwa_strerror(code: int) -> str:
+    return load_library().gfwa_strerror(int(code)).decode()
+
+
+def gfwa_version() -> int:
+    return int(load_library().gfwa_version())
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise GfwaError(code, gfwa_strerror(code))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return GFWA_BF16
+    if t.dtype == torch.float32:
+        return GFWA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}: bfloat16 or float32")
+
+
+def _need(t: torch.Tensor, shape, dtype, name: str) -> None:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def gfwa_gate_prefix(alpha: torch.Tensor, c: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """c[b,h,t] = sum_{q<=t} alpha[b,h,q];  alpha, c: [B,H,N] fp32 on the GPU."""
+    if alpha.dim() != 3:
+        raise ValueError("alpha must be [B,H,N]")
+    B, H, N = alpha.shape
+    _need(alpha, (B, H, N), torch.float32, "alpha")
+    if c is None:
+        c = torch.empty_like(alpha)
+    _need(c, (B, H, N), torch.float32, "c")
+    _check(load_library().gfwa_gate_prefix(alpha.data_ptr(), c.data_ptr(), B, H, N, _stream()))
+    return c
+
+
+def gfwa_forward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, c: torch.Tensor, w: int,
+                 scale: float, O: Optional[torch.Tensor] = None,
+                 L: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """O, L of the gated sliding-window attention; Q,K,V: [B,H,N,d], c: [B,H,N] fp32."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B,H,N,d]")
+    B, H, N, d = Q.shape
+    dt = _dt(Q)
+    for name, t in (("Q", Q), ("K", K), ("V", V)):
+        _need(t, (B, H, N, d), Q.dtype, name)
+    _need(c, (B, H, N), torch.float32, "c")
+    if O is None:
+        O = torch.empty_like(Q)
+    if L is None:
+        L = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _need(O, (B, H, N, d), Q.dtype, "O")
+    _need(L, (B, H, N), torch.float32, "L")
+    _check(load_library().gfwa_forward(dt, Q.data_ptr(), K.data_ptr(), V.data_ptr(), c.data_ptr(),
+                                       O.data_ptr(), L.data_ptr(), B, H, N, d, int(w), float(scale),
+                                       _stream()))
+    return O, L
+
+
+def gfwa_backward_workspace_bytes(dtype: torch.dtype, B: int, H: int, N: int, d: int, w: int) -> int:
+    dt = GFWA_BF16 if dtype == torch.bfloat16 else GFWA_F32
+    return int(load_library().gfwa_backward_workspace_bytes(dt, B, H, N, d, int(w)))
+
+
+def gfwa_backward(Q, K, V, O, dO, c, L, w: int, scale: float, workspace: Optional[torch.Tensor] = None,
+                  dQ=None, dK=None, dV=None, dalpha=None):
+    """dQ, dK, dV ([B,H,N,d], dtype of Q) and dalpha ([B,H,N] fp32) from the saved O and L."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B,H,N,d]")
+    B, H, N, d = Q.shape
+    dt = _dt(Q)
+    for name, t in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
+        _need(t, (B, H, N, d), Q.dtype, name)
+    _need(c, (B, H, N), torch.float32, "c")
+    _need(L, (B, H, N), torch.float32, "L")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    dalpha = torch.empty((B, H, N), dtype=torch.float32, device=Q.device) if dalpha is None else dalpha
+    for name, t in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _need(t, (B, H, N, d), Q.dtype, name)
+    _need(dalpha, (B, H, N), torch.float32, "dalpha")
+    need = gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(load_library().gfwa_backward(dt, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                        dO.data_ptr(), c.data_ptr(), L.data_ptr(), dQ.data_ptr(),
+                                        dK.data_ptr(), dV.data_ptr(), dalpha.data_ptr(),
+                                        workspace.data_ptr(), ws_bytes, B, H, N, d, int(w), float(scale),
+                                        _stream()))
+    return dQ, dK, dV, dalpha
+
+
+def gfwa_profile_enable(on: bool) -> None:
+    """Start (clearing old records) or stop per-kernel HIP-event timing inside the library."""
+    _check(load_library().gfwa_profile_enable(1 if on else 0))
+
+
+def gfwa_profile_read() -> dict:
+    """{kernel name: (total ms, launches)} for the launches recorded since profiling was enabled."""
+    ms = (ctypes.c_float * N_KERNELS)()
+    cnt = (ctypes.c_int * N_KERNELS)()
+    _check(load_library().gfwa_profile_read(ms, cnt, N_KERNELS))
+    return {gfwa_profile_kernel_name(k): (float(ms[k]), int(cnt[k])) for k in range(N_KERNELS)}
+
+
+def gfwa_profile_kernel_name(k: int) -> str:
+    return load_library().gfwa_profile_kernel_name(int(k)).decode()

@@ -1,0 +1,170 @@
+// C ABI of libgfwa (see include/gfwa.h): argument validation and dispatch.  No device memory is
+// allocated here; everything is enqueued on the caller's stream.
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/gfwa.h"
+#include "gfwa_internal.h"
+
+namespace gfwa {
+
+static thread_local char g_hip_msg[256] = "no HIP error recorded";
+
+static int hip_status(hipError_t e) {
+    if (e == hipSuccess) return GFWA_OK;
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d: %s", (int)e, hipGetErrorString(e));
+    return GFWA_ERR_HIP;
+}
+
+static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Sizes every entry point shares.  Tile indices and per-head offsets are 32-bit in the kernels.
+static int check_dims(int B, int H, int N, int d, int w, bool need_d) {
+    if (B <= 0 || H <= 0 || N <= 0) return GFWA_ERR_DIM;
+    if (need_d && (d <= 0 || w < 1)) return GFWA_ERR_DIM;
+    const long long bh = (long long)B * H;
+    if (bh > (1LL << 24) || (long long)N > (1LL << 24)) return GFWA_ERR_DIM;
+    if (bh * ((N + 31) / 32) > 0x7fffffffLL) return GFWA_ERR_DIM;
+    if (need_d && d != 64 && d != 128) return GFWA_ERR_UNSUPPORTED;
+    return GFWA_OK;
+}
+
+// ---- optional per-kernel timing with HIP events on the caller's stream ----
+namespace {
+constexpr int kMaxRecords = 8192;
+struct ProfRecord { int kernel; hipEvent_t start, stop; };
+struct ProfState {
+    bool on = false;
+    int used = 0;
+    int created = 0;
+    ProfRecord rec[kMaxRecords];
+};
+ProfState g_prof;
+}  // namespace
+
+ProfScope::ProfScope(int kernel, hipStream_t s) : slot_(-1), s_(s) {
+    if (!g_prof.on || g_prof.used >= kMaxRecords) return;
+    const int i = g_prof.used;
+    if (i >= g_prof.created) {
+        if (hipEventCreate(&g_prof.rec[i].start) != hipSuccess) return;
+        if (hipEventCreate(&g_prof.rec[i].stop) != hipSuccess) return;
+        g_prof.created = i + 1;
+    }
+    g_prof.rec[i].kernel = kernel;
+    g_prof.used = i + 1;
+    slot_ = i;
+    (void)hipEventRecord(g_prof.rec[i].start, s_);
+}
+ProfScope::~ProfScope() {
+    if (slot_ >= 0) (void)hipEventRecord(g_prof.rec[slot_].stop, s_);
+}
+
+int fwd_variant() {
+    const char* e = getenv("GFWA_FWD_VARIANT");
+    return e ? atoi(e) : 0;
+}
+
+}  // namespace gfwa
+
+using namespace gfwa;
+
+extern "C" {
+
+int gfwa_gate_prefix(const float* alpha, float* c, int B, int H, int N, gfwa_stream_t stream) {
+    if (!alpha || !c) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, 0, 1, false)) return r;
+    if (!aligned(alpha, 4) || !aligned(c, 4)) return GFWA_ERR_ALIGN;
+    return hip_status(gate_prefix(alpha, c, B * H, N, stream));
+}
+
+int gfwa_forward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const float* c, void* O,
+                 float* L, int B, int H, int N, int d, int w, float scale, gfwa_stream_t stream) {
+    if (!Q || !K || !V || !c || !O || !L) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, d, w, true)) return r;
+    if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(c, 4) ||
+        !aligned(L, 4))
+        return GFWA_ERR_ALIGN;
+    if (dt == GFWA_F32)
+        return hip_status(forward_f32((const float*)Q, (const float*)K, (const float*)V, c, (float*)O, L,
+                                      B, H, N, d, w, scale, stream));
+    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, fwd_variant(), stream));
+}
+
+size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
+    if (check_dims(B, H, N, d, w, true) != GFWA_OK) return 0;
+    if (dt != GFWA_BF16 && dt != GFWA_F32) return 0;
+    // D, dc_col, dc_row: three fp32 vectors of B*H*N, each padded to 256 bytes
+    const size_t one = (((size_t)B * H * N * sizeof(float)) + 255) & ~(size_t)255;
+    return 3 * one;
+}
+
+int gfwa_backward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const void* O,
+                  const void* dO, const float* c, const float* L, void* dQ, void* dK, void* dV,
+                  float* dalpha, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, int w,
+                  float scale, gfwa_stream_t stream) {
+    if (!Q || !K || !V || !O || !dO || !c || !L || !dQ || !dK || !dV || !dalpha) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, d, w, true)) return r;
+    if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
+    const void* mats[] = {Q, K, V, O, dO, dQ, dK, dV};
+    for (const void* p : mats)
+        if (!aligned(p, 16)) return GFWA_ERR_ALIGN;
+    if (!aligned(c, 4) || !aligned(L, 4) || !aligned(dalpha, 4)) return GFWA_ERR_ALIGN;
+    const size_t need = gfwa_backward_workspace_bytes(dt, B, H, N, d, w);
+    if (!workspace || workspace_bytes < need) return GFWA_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return GFWA_ERR_ALIGN;
+    float* ws = (float*)workspace;
+    if (dt == GFWA_F32)
+        return hip_status(backward_f32((const float*)Q, (const float*)K, (const float*)V, (const float*)O,
+                                       (const float*)dO, c, L, (float*)dQ, (float*)dK, (float*)dV, dalpha,
+                                       ws, B, H, N, d, w, scale, stream));
+    return hip_status(backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, d, w, scale, stream));
+}
+
+const char* gfwa_strerror(int code) {
+    switch (code) {
+        case GFWA_OK: return "ok";
+        case GFWA_ERR_NULL: return "a required pointer is NULL";
+        case GFWA_ERR_DIM: return "invalid size: B, H, N, d must be > 0, w >= 1, within index range";
+        case GFWA_ERR_UNSUPPORTED: return "unsupported head dimension (64 or 128) or dtype";
+        case GFWA_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes matrices, 4 bytes vectors)";
+        case GFWA_ERR_WORKSPACE: return "workspace missing or smaller than gfwa_backward_workspace_bytes()";
+        case GFWA_ERR_HIP: return g_hip_msg;
+        default: return "unknown status code";
+    }
+}
+
+int gfwa_version(void) { return 100; }
+
+int gfwa_profile_enable(int on) {
+    g_prof.on = on != 0;
+    g_prof.used = 0;
+    return GFWA_OK;
+}
+
+int gfwa_profile_read(float* total_ms, int* launches, int n) {
+    if (!total_ms || !launches) return GFWA_ERR_NULL;
+    if (n < kKernCount) return GFWA_ERR_DIM;
+    for (int k = 0; k < n; ++k) {
+        total_ms[k] = 0.f;
+        launches[k] = 0;
+    }
+    for (int i = 0; i < g_prof.used; ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.rec[i].stop);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.rec[i].start, g_prof.rec[i].stop);
+        if (e != hipSuccess) return hip_status(e);
+        total_ms[g_prof.rec[i].kernel] += ms;
+        launches[g_prof.rec[i].kernel] += 1;
+    }
+    return GFWA_OK;
+}
+
+const char* gfwa_profile_kernel_name(int k) {
+    static const char* names[kKernCount] = {"gate_prefix_scan", "forward", "bwd_rowdot", "bwd_dkv", "bwd_dq",
+                                            "gate_grad_scan"};
+    return (k >= 0 && k < kKernCount) ? names[k] : "";
+}
+
+}  // extern "C"

@@ -1,0 +1,443 @@
+// GatedFWA backward for bf16 storage on gfx950 (paper App. E.2 / Alg. 3, re-designed for CDNA4).
+//
+// Four launches, no atomics, deterministic:
+//   1. rowdot:   D_t = <O_t, dO_t>                                   (HBM-bound)
+//   2. dkv:      key-stationary.  A wave keeps 32 keys of K and V in registers as MFMA B operands
+//                and streams 64-query tiles of Q and dO through LDS:
+//                  S[q][k]   = Q (A, LDS)       x K^T (B, regs)      P  = exp2(x - L)
+//                  dP[q][k]  = dO (A, LDS)      x V^T (B, regs)      dS = P (dP - D)
+//                  dV^T[dd][k] += dO^T (A, LDS transposing read) x P  (B = accumulator registers)
+//                  dK^T[dd][k] += Q^T  (A, LDS transposing read) x dS (B = accumulator registers)
+//                plus the column sums of dS.  A lane owns one key.
+//   3. dq:       query-stationary, the forward's layout.  A lane owns one query:
+//                  S^T[k][q] = K (A, LDS) x Q^T (B, regs)   dP^T[k][q] = V (A, LDS) x dO^T (B, regs)
+//                  dQ^T[dd][q] += K^T (A, LDS transposing read) x dS^T (B = accumulator registers)
+//                plus the row sums of dS.
+//   4. reverse scan of (column sums - row sums) -> dalpha   (gate_scan.hip)
+// The row sums are analytically zero but are kept: with D formed from the rounded O they carry
+// exactly the error that would otherwise accumulate over the whole suffix in the reverse scan.
+#include "gfwa_device.h"
+#include "gfwa_internal.h"
+#include "tile_stage.h"
+
+namespace gfwa {
+
+constexpr float kPosBig = 1.0e30f;
+
+// ------------------------------------------------------------------------------------------
+// 1. D_t = <O_t, dO_t>
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void rowdot_bf16_kernel(const bf16_t* __restrict__ O,
+                                                          const bf16_t* __restrict__ dO,
+                                                          float* __restrict__ Dv, long rows) {
+    constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
+    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+    const long r = gid / LPR;
+    const int part = (int)(gid % LPR);
+    float acc = 0.f;
+    if (r < rows) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(O + r * D + part * 8);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + r * D + part * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf((float)a[e], (float)b[e], acc);
+    }
+#pragma unroll
+    for (int d = LPR / 2; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (r < rows && part == 0) Dv[r] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// 2. dK, dV, column sums: key-stationary
+// ------------------------------------------------------------------------------------------
+template <int D>
+struct DkvSmem {
+    TilePairSmem<D> qg;                 // a = Q tile, b = dO tile
+    alignas(16) float lsub[2][kTileRows];  // L_t*log2e + (c_t - c_base)*log2e, +big for rows >= N
+    alignas(16) float dvec[2][kTileRows];  // D_t
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
+    const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
+    float* __restrict__ dc_col, int N, int w, float scale, int num_ktiles, int total_tiles) {
+    constexpr int BK = 128;  // keys per workgroup, 32 per wave
+    constexpr int KC = D / 16, DB = D / 32;
+    __shared__ DkvSmem<D> sm;
+
+    const int tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bh = tile / num_ktiles;
+    const int k0 = (tile % num_ktiles) * BK;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int h = lane >> 5, lk = lane & 31;
+    const float scale_log2 = scale * kLog2e;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const bf16_t* Qh = Q + head_off;
+    const bf16_t* Gh = dO + head_off;
+    const float* ch = c + (size_t)bh * N;
+    const float* Lh = L + (size_t)bh * N;
+    const float* Dh = Dv + (size_t)bh * N;
+    const float cbase = ch[k0];
+
+    const int kw0 = k0 + 32 * wv;  // first key of this wave
+    const int key = kw0 + lk;
+
+    // K^T and V^T fragments (B operands: column = key, k = head dimension), resident
+    bf16x8 kf[KC], vf[KC];
+    float ckl = 0.f;
+    if (key < N) {
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)key * D + 16 * kc + 8 * h);
+            vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)key * D + 16 * kc + 8 * h);
+        }
+        ckl = (ch[key] - cbase) * kLog2e;
+    } else {
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            kf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            vf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+
+    f32x16 dk_acc[DB], dv_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            dk_acc[db][v] = 0.f;
+            dv_acc[db][v] = 0.f;
+        }
+    float colsum = 0.f;
+
+    // queries that can see a key of this tile: k0 <= t <= min(N-1, k0+BK-1+w-1)
+    const long t_hi_l = min((long)N - 1, (long)k0 + BK - 1 + (long)w - 1);
+    const int t_hi = (int)t_hi_l;
+    const int i_lo = k0 / kTileRows, i_hi = t_hi / kTileRows;
+
+    TilePairRegs<D> stage;
+    float ls_stage = kPosBig, d_stage = 0.f;
+    auto load_vec = [&](int row0) {
+        if (tid < kTileRows) {
+            const int t = row0 + tid;
+            if (t < N) {
+                ls_stage = Lh[t] * kLog2e + (ch[t] - cbase) * kLog2e;
+                d_stage = Dh[t];
+            } else {
+                ls_stage = kPosBig;
+                d_stage = 0.f;
+            }
+        }
+    };
+    auto store_vec = [&](int buf) {
+        if (tid < kTileRows) {
+            sm.lsub[buf][tid] = ls_stage;
+            sm.dvec[buf][tid] = d_stage;
+        }
+    };
+    stage.load(Qh, Gh, i_lo * kTileRows, N, tid);
+    load_vec(i_lo * kTileRows);
+    stage.store(sm.qg, 0, tid);
+    store_vec(0);
+    __syncthreads();
+
+    for (int i = i_lo; i <= i_hi; ++i) {
+        const int buf = (i - i_lo) & 1;
+        if (i < i_hi) {
+            stage.load(Qh, Gh, (i + 1) * kTileRows, N, tid);
+            load_vec((i + 1) * kTileRows);
+        }
+        const char* qt = sm.qg.a[buf];
+        const char* gt = sm.qg.b[buf];
+#pragma unroll
+        for (int sb = 0; sb < kTileRows / 32; ++sb) {
+            const int qb0 = i * kTileRows + 32 * sb;
+            const bool act = (kw0 <= qb0 + 31) && (kw0 + 31 > qb0 - w) && (kw0 < N) && (qb0 < N);
+            if (!act) continue;
+            const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
+
+            f32x16 s, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                s[v] = 0.f;
+                dp[v] = 0.f;
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 qa = lds_read_frag<D>(qt, 32 * sb, kc, lane);
+                s = mfma32(qa, kf[kc], s);
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 ga = lds_read_frag<D>(gt, 32 * sb, kc, lane);
+                dp = mfma32(ga, vf[kc], dp);
+            }
+            // per-row vectors of the 16 query rows this lane sees
+            f32x4 lsv[4], dvv[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                lsv[g] = *reinterpret_cast<const f32x4*>(&sm.lsub[buf][32 * sb + 8 * g + 4 * h]);
+                dvv[g] = *reinterpret_cast<const f32x4*>(&sm.dvec[buf][32 * sb + 8 * g + 4 * h]);
+            }
+            float p[16], ds[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float x = fmaf(s[v], scale_log2, ckl - lsv[v >> 2][v & 3]);
+                p[v] = fast_exp2(x);
+            }
+            if (!full) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = qb0 + acc_row(v, h);
+                    const bool keep = (key <= t) && (key > t - w);
+                    p[v] = keep ? p[v] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                ds[v] = p[v] * (dp[v] - dvv[v >> 2][v & 3]);
+                colsum += ds[v];
+            }
+            bf16x8 pf[2], dsf[2];
+            acc_to_bfrag(p, pf);
+            acc_to_bfrag(ds, dsf);
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 gT = lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane);
+                    dv_acc[db] = mfma32(gT, pf[c2], dv_acc[db]);
+                    const bf16x8 qT = lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane);
+                    dk_acc[db] = mfma32(qT, dsf[c2], dk_acc[db]);
+                }
+        }
+        if (i < i_hi) {
+            stage.store(sm.qg, buf ^ 1, tid);
+            store_vec(buf ^ 1);
+        }
+        __syncthreads();
+    }
+
+    const float cs = xhalf_sum(colsum);
+    if (key < N) {
+        bf16_t* dkrow = dK + head_off + (size_t)key * D;
+        bf16_t* dvrow = dV + head_off + (size_t)key * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 k4 = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale,
+                            dk_acc[db][4 * g + 2] * scale, dk_acc[db][4 * g + 3] * scale};
+                f32x4 v4 = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2],
+                            dv_acc[db][4 * g + 3]};
+                *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(k4, bf16x4);
+                *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(v4, bf16x4);
+            }
+        if (h == 0) dc_col[(size_t)bh * N + key] = cs;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// 3. dQ, row sums: query-stationary
+// ------------------------------------------------------------------------------------------
+template <int D>
+struct DqSmem {
+    TilePairSmem<D> kv;
+    alignas(16) float ck[2][kTileRows];
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
+    const float* __restrict__ Dv, bf16_t* __restrict__ dQ, float* __restrict__ dc_row, int N, int w,
+    float scale, int num_qtiles, int total_tiles) {
+    constexpr int BR = 128;
+    constexpr int KC = D / 16, DB = D / 32;
+    __shared__ DqSmem<D> sm;
+
+    const int tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bh = tile / num_qtiles;
+    const int q0 = (tile % num_qtiles) * BR;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int h = lane >> 5, lq = lane & 31;
+    const float scale_log2 = scale * kLog2e;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const bf16_t* Kh = K + head_off;
+    const bf16_t* Vh = V + head_off;
+    const float* ch = c + (size_t)bh * N;
+    const float cbase = ch[q0];
+
+    const int qw0 = q0 + 32 * wv;
+    const int t = qw0 + lq;
+
+    bf16x8 qf[KC], gf[KC];
+    float lsub = kPosBig, dt = 0.f;
+    if (t < N) {
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)t * D + 16 * kc + 8 * h);
+            gf[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)t * D + 16 * kc + 8 * h);
+        }
+        lsub = L[(size_t)bh * N + t] * kLog2e + (ch[t] - cbase) * kLog2e;
+        dt = Dv[(size_t)bh * N + t];
+    } else {
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            qf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            gf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+
+    f32x16 dq_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dq_acc[db][v] = 0.f;
+    float rowsum = 0.f;
+
+    const int k_lo = max(0, q0 - w + 1);
+    const int k_hi = min(N, q0 + BR) - 1;
+    const int j_lo = k_lo / kTileRows, j_hi = k_hi / kTileRows;
+
+    TilePairRegs<D> stage;
+    float ck_stage = 0.f;
+    auto load_ck = [&](int key0) {
+        if (tid < kTileRows) {
+            const int key = key0 + tid;
+            ck_stage = key < N ? (ch[key] - cbase) * kLog2e : 0.f;
+        }
+    };
+    stage.load(Kh, Vh, j_lo * kTileRows, N, tid);
+    load_ck(j_lo * kTileRows);
+    stage.store(sm.kv, 0, tid);
+    if (tid < kTileRows) sm.ck[0][tid] = ck_stage;
+    __syncthreads();
+
+    for (int j = j_lo; j <= j_hi; ++j) {
+        const int buf = (j - j_lo) & 1;
+        if (j < j_hi) {
+            stage.load(Kh, Vh, (j + 1) * kTileRows, N, tid);
+            load_ck((j + 1) * kTileRows);
+        }
+        const char* kt = sm.kv.a[buf];
+        const char* vt = sm.kv.b[buf];
+#pragma unroll
+        for (int sb = 0; sb < kTileRows / 32; ++sb) {
+            const int kb0 = j * kTileRows + 32 * sb;
+            const bool act = (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
+            if (!act) continue;
+            const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
+
+            f32x16 s, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                s[v] = 0.f;
+                dp[v] = 0.f;
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 ka = lds_read_frag<D>(kt, 32 * sb, kc, lane);
+                s = mfma32(ka, qf[kc], s);
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 va = lds_read_frag<D>(vt, 32 * sb, kc, lane);
+                dp = mfma32(va, gf[kc], dp);
+            }
+            f32x4 ckv[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                ckv[g] = *reinterpret_cast<const f32x4*>(&sm.ck[buf][32 * sb + 8 * g + 4 * h]);
+            float ds[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float x = fmaf(s[v], scale_log2, ckv[v >> 2][v & 3] - lsub);
+                float p = fast_exp2(x);
+                if (!full) {
+                    const int i = kb0 + acc_row(v, h);
+                    const bool keep = (i <= t) && (i > t - w);
+                    p = keep ? p : 0.f;
+                }
+                ds[v] = p * (dp[v] - dt);
+                rowsum += ds[v];
+            }
+            bf16x8 dsf[2];
+            acc_to_bfrag(ds, dsf);
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 kT = lds_read_tr_frag<D>(kt, 32 * sb + 16 * c2, db, lane);
+                    dq_acc[db] = mfma32(kT, dsf[c2], dq_acc[db]);
+                }
+        }
+        if (j < j_hi) {
+            stage.store(sm.kv, buf ^ 1, tid);
+            if (tid < kTileRows) sm.ck[buf ^ 1][tid] = ck_stage;
+        }
+        __syncthreads();
+    }
+
+    const float rs = xhalf_sum(rowsum);
+    if (t < N) {
+        bf16_t* row = dQ + head_off + (size_t)t * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale,
+                            dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale};
+                *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(q4, bf16x4);
+            }
+        if (h == 0) dc_row[(size_t)bh * N + t] = rs;
+    }
+}
+
+template <int D>
+static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                             const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
+                             float* ws, int B, int H, int N, int w, float scale, hipStream_t s) {
+    const size_t rows = (size_t)B * H * N;
+    const size_t pad = ((rows * sizeof(float) + 255) & ~(size_t)255) / sizeof(float);
+    float* Dv = ws;
+    float* dc_col = ws + pad;
+    float* dc_row = ws + 2 * pad;
+    constexpr int LPR = D / 8;
+    const unsigned dot_blocks = (unsigned)((rows * LPR + 255) / 256);
+    {
+        ProfScope prof(kKernRowDot, s);
+        hipLaunchKernelGGL((rowdot_bf16_kernel<D>), dim3(dot_blocks), dim3(256), 0, s, (const bf16_t*)O,
+                           (const bf16_t*)dO, Dv, (long)rows);
+    }
+    const int nk = (N + 127) / 128;
+    {
+        ProfScope prof(kKernDkv, s);
+        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * H * nk), dim3(kThreads), 0, s,
+                           (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                           (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * H * nk);
+    }
+    const int nq = (N + 127) / 128;
+    {
+        ProfScope prof(kKernDq, s);
+        hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads), 0, s,
+                           (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                           (bf16_t*)dQ, dc_row, N, w, scale, nq, B * H * nq);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return gate_grad_scan(dc_col, dc_row, dalpha, B * H, N, s);
+}
+
+hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                         const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
+                         float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s) {
+    if (d == 128) return launch_bwd<128>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, w, scale, s);
+    return launch_bwd<64>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, w, scale, s);
+}
+
+}  // namespace gfwa

@@ -1,0 +1,42 @@
+// Host-side launch functions behind the C ABI (one per kernel family).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace gfwa {
+
+// c = inclusive prefix sum of alpha along N, one row per (b,h).
+hipError_t gate_prefix(const float* alpha, float* c, int rows, int N, hipStream_t s);
+// dalpha = reverse inclusive prefix sum of (col - row) along N.
+hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
+                          hipStream_t s);
+
+hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
+                        int B, int H, int N, int d, int w, float scale, int variant, hipStream_t s);
+hipError_t forward_f32(const float* Q, const float* K, const float* V, const float* c, float* O,
+                       float* L, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+
+// Workspace layout of the backward: three fp32 vectors of B*H*N: D, dc_col, dc_row.
+hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                         const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
+                         float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+hipError_t backward_f32(const float* Q, const float* K, const float* V, const float* O, const float* dO,
+                        const float* c, const float* L, float* dQ, float* dK, float* dV, float* dalpha,
+                        float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+
+// Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
+enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernCount };
+
+// RAII pair of HIP events around one kernel launch on stream s; a no-op unless profiling is on.
+struct ProfScope {
+    ProfScope(int kernel, hipStream_t s);
+    ~ProfScope();
+    int slot_;
+    hipStream_t s_;
+};
+
+// Tuning knob read from the environment at each call (GFWA_FWD_VARIANT): 0 = 32 queries per wave,
+// 1 = 64 queries per wave.
+int fwd_variant();
+
+}  // namespace gfwa

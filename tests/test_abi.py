@@ -1,0 +1,86 @@
+"""The C-ABI library: it loads without a GPU, exports every symbol the header declares, and
+rejects bad arguments on the host before anything is launched (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2512_07782_amd as g
+    return g.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gfwa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gfwa_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert names == sorted(["gfwa_gate_prefix", "gfwa_forward", "gfwa_backward_workspace_bytes",
+                            "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
+                            "gfwa_profile_read", "gfwa_profile_kernel_name"])
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_exposes_the_same_names():
+    import paper_2512_07782_amd as g
+    for n in declared_functions():
+        assert callable(getattr(g, n)), n
+
+
+def test_version_and_strerror(lib):
+    import paper_2512_07782_amd as g
+    assert g.gfwa_version() >= 100
+    assert g.gfwa_strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert len(g.gfwa_strerror(code)) > 3
+    assert "unknown" in g.gfwa_strerror(-99)
+
+
+def test_argument_validation_on_host(lib):
+    P = ctypes.c_void_p
+    good = P(0x1000)
+    odd = P(0x1004)
+    f = ctypes.c_float(0.125)
+    # gate prefix
+    assert lib.gfwa_gate_prefix(None, good, 1, 1, 8, None) == -1
+    assert lib.gfwa_gate_prefix(good, good, 0, 1, 8, None) == -2
+    assert lib.gfwa_gate_prefix(good, good, 1, 1, -3, None) == -2
+    assert lib.gfwa_gate_prefix(P(0x1002), good, 1, 1, 8, None) == -4
+    # forward
+    args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
+                         kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]
+    assert lib.gfwa_forward(*args(Q=None)) == -1
+    assert lib.gfwa_forward(*args(B=0)) == -2
+    assert lib.gfwa_forward(*args(w=0)) == -2
+    assert lib.gfwa_forward(*args(d=96)) == -3
+    assert lib.gfwa_forward(*args(dt=7)) == -3
+    assert lib.gfwa_forward(*args(Q=odd)) == -4
+    # backward
+    need = lib.gfwa_backward_workspace_bytes(0, 2, 3, 100, 64, 16)
+    assert need >= 3 * 2 * 3 * 100 * 4
+    assert lib.gfwa_backward_workspace_bytes(0, 2, 3, 100, 80, 16) == 0
+    assert lib.gfwa_backward_workspace_bytes(0, 0, 3, 100, 64, 16) == 0
+    bargs = lambda **kw: [0] + [kw.get("Q", good)] + [good] * 10 + [kw.get("ws", good), kw.get("wsb", need),
+                                                                   2, 3, 100, kw.get("d", 64), 16, f, None]
+    assert lib.gfwa_backward(*bargs(Q=None)) == -1
+    assert lib.gfwa_backward(*bargs(d=100)) == -3
+    assert lib.gfwa_backward(*bargs(ws=None)) == -5
+    assert lib.gfwa_backward(*bargs(wsb=need - 1)) == -5
+    assert lib.gfwa_backward(*bargs(Q=odd)) == -4
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2512_07782_amd as g
+    a = torch.zeros(1, 1, 8)
+    with pytest.raises(ValueError):
+        g.gfwa_gate_prefix(a)
