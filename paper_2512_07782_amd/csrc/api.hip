@@ -139,7 +139,7 @@ int gfwa_version(void) { return 100; }
 
 int gfwa_profile_enable(int on) {
     g_prof.on = on != 0;
-    g_prof.used = 0;
+    if (g_prof.on) g_prof.used = 0;  // records stay readable after profiling is switched off
     return GFWA_OK;
 }
 
