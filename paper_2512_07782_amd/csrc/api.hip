@@ -89,7 +89,10 @@ int gfwa_forward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, c
     if (dt == GFWA_F32)
         return hip_status(forward_f32((const float*)Q, (const float*)K, (const float*)V, c, (float*)O, L,
                                       B, H, N, d, w, scale, stream));
-    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, fwd_variant(), stream));
+    const int variant = fwd_variant();
+    if (d == 128 && (variant == 2 || variant == 3))
+        return hip_status(forward_bf16_pipe(Q, K, V, c, O, L, B, H, N, w, scale, variant == 2 ? 2 : 1, stream));
+    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, variant, stream));
 }
 
 size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
