@@ -48,39 +48,6 @@ struct PipeSmem {
     alignas(16) float g[2][kKb];         // (c - c_base) / scale
 };
 
-// Direct global->LDS loads: every active lane p fetches `bytes` from  sbase + voff  and the data
-// lands at lds_base + bytes*p (lds_base is wave-uniform and travels in M0, which is saved and
-// restored because the compiler may keep its own value there).  Issued through inline assembly on
-// purpose: their completion is tracked by hand with vmcnt waits in front of the workgroup barrier,
-// whereas loads the compiler knows about would make it wait for all of them before every LDS read,
-// which would undo the prefetch.
-__device__ __forceinline__ void dma16(const void* sbase, unsigned voff, const void* lds_base) {
-    const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;  // LDS pointers are 32-bit offsets
-    unsigned saved;
-    asm volatile(
-        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-        : "=&s"(saved)
-        : "s"(lds_addr), "v"(voff), "s"(sbase)
-        : "memory");
-}
-__device__ __forceinline__ void dma4(const void* sbase, unsigned voff, const void* lds_base) {
-    const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;
-    unsigned saved;
-    asm volatile(
-        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b32 m0, %0"
-        : "=&s"(saved)
-        : "s"(lds_addr), "v"(voff), "s"(sbase)
-        : "memory");
-}
-
-// s_waitcnt that waits only for vmcnt <= n (gfx9 encoding: expcnt and lgkmcnt fields left at max)
-constexpr int vmcnt_only(int n) { return 0x0f70 | (n & 0xf) | ((n >> 4) << 14); }
-
-// Empty volatile asm that consumes and re-defines a register: instruction selection keeps volatile
-// asm in program order with the scheduling fences, so values routed through it are computed on
-// this side of the next fence instead of drifting to their first use (and loop-invariant values
-// pinned once are kept in registers instead of being recomputed).
-#define GFWA_PIN(x) asm volatile("" : "+v"(x))
 #define GFWA_FENCE() __builtin_amdgcn_sched_barrier(0)
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
