@@ -60,11 +60,6 @@ ProfScope::~ProfScope() {
     if (slot_ >= 0) (void)hipEventRecord(g_prof.rec[slot_].stop, s_);
 }
 
-int fwd_variant() {
-    const char* e = getenv("GFWA_FWD_VARIANT");
-    return e ? atoi(e) : 0;
-}
-
 }  // namespace gfwa
 
 using namespace gfwa;
@@ -89,10 +84,7 @@ int gfwa_forward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, c
     if (dt == GFWA_F32)
         return hip_status(forward_f32((const float*)Q, (const float*)K, (const float*)V, c, (float*)O, L,
                                       B, H, N, d, w, scale, stream));
-    const int variant = fwd_variant();
-    if (d == 128 && (variant == 2 || variant == 3))
-        return hip_status(forward_bf16_pipe(Q, K, V, c, O, L, B, H, N, w, scale, variant == 2 ? 2 : 1, stream));
-    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, variant, stream));
+    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, stream));
 }
 
 size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {

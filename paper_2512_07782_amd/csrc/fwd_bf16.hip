@@ -248,8 +248,7 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
 }
 
 hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
-                        int B, int H, int N, int d, int w, float scale, int variant, hipStream_t s) {
-    (void)variant;
+                        int B, int H, int N, int d, int w, float scale, hipStream_t s) {
     if (d == 128) return launch_fwd<128>(Q, K, V, c, O, L, B, H, N, w, scale, s);
     return launch_fwd<64>(Q, K, V, c, O, L, B, H, N, w, scale, s);
 }

@@ -12,10 +12,7 @@ hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalph
                           hipStream_t s);
 
 hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
-                        int B, int H, int N, int d, int w, float scale, int variant, hipStream_t s);
-// Software-pipelined forward (d = 128 only); occupancy = waves per SIMD the kernel is built for.
-hipError_t forward_bf16_pipe(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
-                             int B, int H, int N, int w, float scale, int occupancy, hipStream_t s);
+                        int B, int H, int N, int d, int w, float scale, hipStream_t s);
 hipError_t forward_f32(const float* Q, const float* K, const float* V, const float* c, float* O,
                        float* L, int B, int H, int N, int d, int w, float scale, hipStream_t s);
 
@@ -38,8 +35,5 @@ struct ProfScope {
     hipStream_t s_;
 };
 
-// Tuning knob read from the environment at each call (GFWA_FWD_VARIANT): 0 = 32 queries per wave,
-// 1 = 64 queries per wave.
-int fwd_variant();
 
 }  // namespace gfwa
