@@ -3,7 +3,7 @@
 // Four launches, no atomics, deterministic:
 //   1. rowdot:   D_t = <O_t, dO_t>                                   (HBM-bound)
 //   2. dkv:      key-stationary.  A wave keeps 32 keys of K and V in registers as MFMA B operands
-//                and streams 64-query tiles of Q and dO through LDS:
+//                and streams 64-query tiles of Q and dO through LDS (direct global->LDS loads):
 //                  S[q][k]   = Q (A, LDS)       x K^T (B, regs)      P  = exp2(x - L)
 //                  dP[q][k]  = dO (A, LDS)      x V^T (B, regs)      dS = P (dP - D)
 //                  dV^T[dd][k] += dO^T (A, LDS transposing read) x P  (B = accumulator registers)
@@ -14,6 +14,9 @@
 //                  dQ^T[dd][q] += K^T (A, LDS transposing read) x dS^T (B = accumulator registers)
 //                plus the row sums of dS.
 //   4. reverse scan of (column sums - row sums) -> dalpha   (gate_scan.hip)
+// In both kernels the row- (dkv) or key- (dq) dependent part of the exponent rides in the MFMA
+// accumulator (it is initialised from an LDS vector before the product), the lane-constant part is
+// the addend of the single fused multiply-add in front of exp2.
 // The row sums are analytically zero but are kept: with D formed from the rounded O they carry
 // exactly the error that would otherwise accumulate over the whole suffix in the reverse scan.
 #include "gfwa_device.h"
@@ -52,8 +55,8 @@ __global__ __launch_bounds__(256) void rowdot_bf16_kernel(const bf16_t* __restri
 // ------------------------------------------------------------------------------------------
 template <int D>
 struct DkvSmem {
-    TilePairSmem<D> qg;                 // a = Q tile, b = dO tile
-    alignas(16) float lsub[2][kTileRows];  // L_t*log2e + (c_t - c_base)*log2e, +big for rows >= N
+    TilePairSmem<D> qg;                    // a = Q tile, b = dO tile
+    alignas(16) float nl[2][kTileRows];    // -(L_t + c_t - c_base) / scale; -big for rows >= N
     alignas(16) float dvec[2][kTileRows];  // D_t
 };
 
@@ -70,13 +73,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     const int tile = xcd_remap(blockIdx.x, total_tiles);
     const int bh = tile / num_ktiles;
     const int k0 = (tile % num_ktiles) * BK;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, lk = lane & 31;
-    const float scale_log2 = scale * kLog2e;
+    const float sl = scale * kLog2e;
+    const float inv_scale = 1.0f / scale;
 
     const size_t head_off = (size_t)bh * N * D;
-    const bf16_t* Qh = Q + head_off;
-    const bf16_t* Gh = dO + head_off;
+    const char* Qh = reinterpret_cast<const char*>(Q + head_off);
+    const char* Gh = reinterpret_cast<const char*>(dO + head_off);
     const float* ch = c + (size_t)bh * N;
     const float* Lh = L + (size_t)bh * N;
     const float* Dh = Dv + (size_t)bh * N;
@@ -87,21 +92,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
 
     // K^T and V^T fragments (B operands: column = key, k = head dimension), resident
     bf16x8 kf[KC], vf[KC];
-    float ckl = 0.f;
-    if (key < N) {
+    {
+        const size_t roff = head_off + (size_t)min(key, N - 1) * D + 8 * h;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            kf[kc] = *reinterpret_cast<const bf16x8*>(K + head_off + (size_t)key * D + 16 * kc + 8 * h);
-            vf[kc] = *reinterpret_cast<const bf16x8*>(V + head_off + (size_t)key * D + 16 * kc + 8 * h);
-        }
-        ckl = (ch[key] - cbase) * kLog2e;
-    } else {
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            kf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            vf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            kf[kc] = *reinterpret_cast<const bf16x8*>(K + roff + 16 * kc);
+            vf[kc] = *reinterpret_cast<const bf16x8*>(V + roff + 16 * kc);
         }
     }
+    const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
 
     f32x16 dk_acc[DB], dv_acc[DB];
 #pragma unroll
@@ -114,41 +113,43 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     float colsum = 0.f;
 
     // queries that can see a key of this tile: k0 <= t <= min(N-1, k0+BK-1+w-1)
-    const long t_hi_l = min((long)N - 1, (long)k0 + BK - 1 + (long)w - 1);
-    const int t_hi = (int)t_hi_l;
+    const int t_hi = (int)min((long)N - 1, (long)k0 + BK - 1 + (long)w - 1);
     const int i_lo = k0 / kTileRows, i_hi = t_hi / kTileRows;
+    const int ifull = N / kTileRows;
 
-    TilePairRegs<D> stage;
-    float ls_stage = kPosBig, d_stage = 0.f;
-    auto load_vec = [&](int row0) {
+    TilePairLoader<D> loader;
+    loader.init(wv, lane);
+    // per-row vectors of query tile i, one row per thread of the first wave
+    float nl_stage = -kPosBig, d_stage = 0.f;
+    auto load_vec = [&](int i) {
         if (tid < kTileRows) {
-            const int t = row0 + tid;
+            const int t = i * kTileRows + tid;
             if (t < N) {
-                ls_stage = Lh[t] * kLog2e + (ch[t] - cbase) * kLog2e;
+                nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
                 d_stage = Dh[t];
             } else {
-                ls_stage = kPosBig;
+                nl_stage = -kPosBig;
                 d_stage = 0.f;
             }
         }
     };
     auto store_vec = [&](int buf) {
         if (tid < kTileRows) {
-            sm.lsub[buf][tid] = ls_stage;
+            sm.nl[buf][tid] = nl_stage;
             sm.dvec[buf][tid] = d_stage;
         }
     };
-    stage.load(Qh, Gh, i_lo * kTileRows, N, tid);
-    load_vec(i_lo * kTileRows);
-    stage.store(sm.qg, 0, tid);
+    loader.load(Qh, Gh, i_lo, ifull, N, sm.qg, 0);
+    load_vec(i_lo);
     store_vec(0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int i = i_lo; i <= i_hi; ++i) {
         const int buf = (i - i_lo) & 1;
         if (i < i_hi) {
-            stage.load(Qh, Gh, (i + 1) * kTileRows, N, tid);
-            load_vec((i + 1) * kTileRows);
+            loader.load(Qh, Gh, i + 1, ifull, N, sm.qg, buf ^ 1);
+            load_vec(i + 1);
         }
         const char* qt = sm.qg.a[buf];
         const char* gt = sm.qg.b[buf];
@@ -159,35 +160,22 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
             if (!act) continue;
             const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
 
+            // S[q][k] starts from the row term of the exponent; dP from zero
             f32x16 s, dp;
+            acc_init_rows(s, sm.nl[buf], 32 * sb, h);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                s[v] = 0.f;
-                dp[v] = 0.f;
-            }
+            for (int v = 0; v < 16; ++v) dp[v] = 0.f;
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 qa = lds_read_frag<D>(qt, 32 * sb, kc, lane);
-                s = mfma32(qa, kf[kc], s);
-            }
+            for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 ga = lds_read_frag<D>(gt, 32 * sb, kc, lane);
-                dp = mfma32(ga, vf[kc], dp);
-            }
-            // per-row vectors of the 16 query rows this lane sees
-            f32x4 lsv[4], dvv[4];
+            for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
+            f32x4 dvv[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                lsv[g] = *reinterpret_cast<const f32x4*>(&sm.lsub[buf][32 * sb + 8 * g + 4 * h]);
+            for (int g = 0; g < 4; ++g)
                 dvv[g] = *reinterpret_cast<const f32x4*>(&sm.dvec[buf][32 * sb + 8 * g + 4 * h]);
-            }
             float p[16], ds[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float x = fmaf(s[v], scale_log2, ckl - lsv[v >> 2][v & 3]);
-                p[v] = fast_exp2(x);
-            }
+            for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
             if (!full) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -208,16 +196,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const bf16x8 gT = lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane);
-                    dv_acc[db] = mfma32(gT, pf[c2], dv_acc[db]);
-                    const bf16x8 qT = lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane);
-                    dk_acc[db] = mfma32(qT, dsf[c2], dk_acc[db]);
+                    dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
+                    dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
                 }
         }
-        if (i < i_hi) {
-            stage.store(sm.qg, buf ^ 1, tid);
-            store_vec(buf ^ 1);
-        }
+        if (i < i_hi) store_vec(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
         __syncthreads();
     }
 
@@ -245,8 +229,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
 // ------------------------------------------------------------------------------------------
 template <int D>
 struct DqSmem {
-    TilePairSmem<D> kv;
-    alignas(16) float ck[2][kTileRows];
+    TilePairSmem<D> kv;                // a = K tile, b = V tile
+    alignas(16) float g[2][kTileRows];  // (c - c_base) / scale
 };
 
 template <int D>
@@ -262,35 +246,36 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     const int tile = xcd_remap(blockIdx.x, total_tiles);
     const int bh = tile / num_qtiles;
     const int q0 = (tile % num_qtiles) * BR;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, lq = lane & 31;
-    const float scale_log2 = scale * kLog2e;
+    const float sl = scale * kLog2e;
+    const float inv_scale = 1.0f / scale;
 
     const size_t head_off = (size_t)bh * N * D;
-    const bf16_t* Kh = K + head_off;
-    const bf16_t* Vh = V + head_off;
+    const char* Kh = reinterpret_cast<const char*>(K + head_off);
+    const char* Vh = reinterpret_cast<const char*>(V + head_off);
     const float* ch = c + (size_t)bh * N;
     const float cbase = ch[q0];
 
     const int qw0 = q0 + 32 * wv;
     const int t = qw0 + lq;
 
+    // Q^T and dO^T fragments (B operands: column = query), resident; rows past N read row N-1 and
+    // get an exponent of -big, i.e. p = 0
     bf16x8 qf[KC], gf[KC];
-    float lsub = kPosBig, dt = 0.f;
+    {
+        const size_t roff = head_off + (size_t)min(t, N - 1) * D + 8 * h;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            qf[kc] = *reinterpret_cast<const bf16x8*>(Q + roff + 16 * kc);
+            gf[kc] = *reinterpret_cast<const bf16x8*>(dO + roff + 16 * kc);
+        }
+    }
+    float nlsub = -kPosBig, dt = 0.f;  // lane-constant part of the exponent: -(L_t + c_t - c_base) log2 e
     if (t < N) {
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            qf[kc] = *reinterpret_cast<const bf16x8*>(Q + head_off + (size_t)t * D + 16 * kc + 8 * h);
-            gf[kc] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)t * D + 16 * kc + 8 * h);
-        }
-        lsub = L[(size_t)bh * N + t] * kLog2e + (ch[t] - cbase) * kLog2e;
+        nlsub = -(L[(size_t)bh * N + t] + (ch[t] - cbase)) * kLog2e;
         dt = Dv[(size_t)bh * N + t];
-    } else {
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            qf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            gf[kc] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
     }
 
     f32x16 dq_acc[DB];
@@ -303,26 +288,25 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     const int k_lo = max(0, q0 - w + 1);
     const int k_hi = min(N, q0 + BR) - 1;
     const int j_lo = k_lo / kTileRows, j_hi = k_hi / kTileRows;
+    const int jfull = N / kTileRows;
 
-    TilePairRegs<D> stage;
-    float ck_stage = 0.f;
-    auto load_ck = [&](int key0) {
-        if (tid < kTileRows) {
-            const int key = key0 + tid;
-            ck_stage = key < N ? (ch[key] - cbase) * kLog2e : 0.f;
-        }
+    TilePairLoader<D> loader;
+    loader.init(wv, lane);
+    auto gate_of = [&](int j) {  // this thread's g value of tile j (threads 0..63)
+        const int key = min(j * kTileRows + tid, N - 1);
+        return (ch[key] - cbase) * inv_scale;
     };
-    stage.load(Kh, Vh, j_lo * kTileRows, N, tid);
-    load_ck(j_lo * kTileRows);
-    stage.store(sm.kv, 0, tid);
-    if (tid < kTileRows) sm.ck[0][tid] = ck_stage;
+    loader.load(Kh, Vh, j_lo, jfull, N, sm.kv, 0);
+    if (tid < kTileRows) sm.g[0][tid] = gate_of(j_lo);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int j = j_lo; j <= j_hi; ++j) {
         const int buf = (j - j_lo) & 1;
+        float g_next = 0.f;
         if (j < j_hi) {
-            stage.load(Kh, Vh, (j + 1) * kTileRows, N, tid);
-            load_ck((j + 1) * kTileRows);
+            loader.load(Kh, Vh, j + 1, jfull, N, sm.kv, buf ^ 1);
+            if (tid < kTileRows) g_next = gate_of(j + 1);
         }
         const char* kt = sm.kv.a[buf];
         const char* vt = sm.kv.b[buf];
@@ -333,31 +317,19 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
             if (!act) continue;
             const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
 
+            // S^T[k][q] starts from the key term of the exponent; dP^T from zero
             f32x16 s, dp;
+            acc_init_rows(s, sm.g[buf], 32 * sb, h);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                s[v] = 0.f;
-                dp[v] = 0.f;
-            }
+            for (int v = 0; v < 16; ++v) dp[v] = 0.f;
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 ka = lds_read_frag<D>(kt, 32 * sb, kc, lane);
-                s = mfma32(ka, qf[kc], s);
-            }
+            for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(kt, 32 * sb, kc, lane), qf[kc], s);
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 va = lds_read_frag<D>(vt, 32 * sb, kc, lane);
-                dp = mfma32(va, gf[kc], dp);
-            }
-            f32x4 ckv[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-                ckv[g] = *reinterpret_cast<const f32x4*>(&sm.ck[buf][32 * sb + 8 * g + 4 * h]);
+            for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(vt, 32 * sb, kc, lane), gf[kc], dp);
             float ds[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float x = fmaf(s[v], scale_log2, ckv[v >> 2][v & 3] - lsub);
-                float p = fast_exp2(x);
+                float p = fast_exp2(fmaf(s[v], sl, nlsub));
                 if (!full) {
                     const int i = kb0 + acc_row(v, h);
                     const bool keep = (i <= t) && (i > t - w);
@@ -371,15 +343,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x8 kT = lds_read_tr_frag<D>(kt, 32 * sb + 16 * c2, db, lane);
-                    dq_acc[db] = mfma32(kT, dsf[c2], dq_acc[db]);
-                }
+                for (int db = 0; db < DB; ++db)
+                    dq_acc[db] = mfma32(lds_read_tr_frag<D>(kt, 32 * sb + 16 * c2, db, lane), dsf[c2], dq_acc[db]);
         }
-        if (j < j_hi) {
-            stage.store(sm.kv, buf ^ 1, tid);
-            if (tid < kTileRows) sm.ck[buf ^ 1][tid] = ck_stage;
-        }
+        if (j < j_hi && tid < kTileRows) sm.g[buf ^ 1][tid] = g_next;
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile j+1 has landed
         __syncthreads();
     }
 
@@ -390,8 +358,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale,
-                            dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale};
+                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale, dq_acc[db][4 * g + 2] * scale,
+                            dq_acc[db][4 * g + 3] * scale};
                 *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(q4, bf16x4);
             }
         if (h == 0) dc_row[(size_t)bh * N + t] = rs;

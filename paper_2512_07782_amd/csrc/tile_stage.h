@@ -1,6 +1,6 @@
-// Cooperative staging of a pair of 64-row bf16 tiles (K and V, or Q and dO) from global memory
-// through registers into swizzled LDS, by a 256-thread workgroup.  Rows at or beyond N read as
-// zero so that masked probabilities never multiply garbage.
+// Staging of a pair of 64-row bf16 tiles (K and V, or Q and dO) from global memory into swizzled
+// LDS by a 256-thread workgroup, with direct global->LDS loads (no staging registers, no LDS
+// stores).  Rows at or beyond N read row N-1: finite data that the band mask keeps out of every sum.
 #pragma once
 #include "gfwa_device.h"
 
@@ -15,34 +15,51 @@ struct TilePairSmem {
     alignas(16) char b[2][kTileRows * D * 2];
 };
 
+// Wave wv fills rows 16wv..16wv+15 of a tile with 1 KB loads; lane p of a load writes row
+// p / chunks-per-row of its group at physical chunk p % chunks-per-row and therefore fetches the
+// logical chunk the swizzle maps there (the swizzle is an involution).
 template <int D>
-struct TilePairRegs {
-    static constexpr int kChunksPerRow = D / 8;
-    static constexpr int kPerThread = kTileRows * kChunksPerRow / kThreads;  // 4 (D=128) or 2 (D=64)
-    uint4 a[kPerThread], b[kPerThread];
+struct TilePairLoader {
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kRowsPerLoad = 1024 / kRowBytes;
+    static constexpr int kChunksPerRow = kRowBytes / 16;
+    static constexpr int kLoadsPerWave = 16 / kRowsPerLoad;
+    static constexpr int kLoadsPerTilePair = 2 * kLoadsPerWave;  // per wave
+    unsigned off[kLoadsPerWave];
+    int wv, lane;
 
-    __device__ __forceinline__ void load(const bf16_t* Ah, const bf16_t* Bh, int row0, int N, int tid) {
+    __device__ __forceinline__ void init(int wave, int lane_) {
+        wv = wave;
+        lane = lane_;
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int id = tid + i * kThreads;
-            const int row = row0 + id / kChunksPerRow, chunk = id % kChunksPerRow;
-            if (row < N) {
-                const size_t off = (size_t)row * D + chunk * 8;
-                a[i] = *reinterpret_cast<const uint4*>(Ah + off);
-                b[i] = *reinterpret_cast<const uint4*>(Bh + off);
-            } else {
-                a[i] = make_uint4(0, 0, 0, 0);
-                b[i] = make_uint4(0, 0, 0, 0);
-            }
+        for (int g = 0; g < kLoadsPerWave; ++g) {
+            const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
+            off[g] = (unsigned)(row * kRowBytes + swz_chunk<D>(row, lane % kChunksPerRow) * 16);
         }
     }
-    __device__ __forceinline__ void store(TilePairSmem<D>& sm, int buf, int tid) const {
+    // tile index j (rows 64j .. 64j+63) of the [N, D] matrices at Ah and Bh into buffer `buf`;
+    // tiles below jfull = N / 64 lie wholly inside the sequence
+    __device__ __forceinline__ void load(const char* Ah, const char* Bh, int j, int jfull, int N,
+                                         TilePairSmem<D>& sm, int buf) const {
+        char* al = sm.a[buf] + 16 * wv * kRowBytes;
+        char* bl = sm.b[buf] + 16 * wv * kRowBytes;
+        if (j < jfull) {
+            const size_t toff = (size_t)j * (kTileRows * kRowBytes);
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int id = tid + i * kThreads;
-            const int row = id / kChunksPerRow, chunk = id % kChunksPerRow;
-            *reinterpret_cast<uint4*>(sm.a[buf] + tile_off<D>(row, chunk)) = a[i];
-            *reinterpret_cast<uint4*>(sm.b[buf] + tile_off<D>(row, chunk)) = b[i];
+            for (int g = 0; g < kLoadsPerWave; ++g) {
+                dma16(Ah + toff, off[g], al + g * 1024);
+                dma16(Bh + toff, off[g], bl + g * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < kLoadsPerWave; ++g) {
+                const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
+                const int r = min(j * kTileRows + row, N - 1);
+                const unsigned o =
+                    (unsigned)r * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, lane % kChunksPerRow) * 16);
+                dma16(Ah, o, al + g * 1024);
+                dma16(Bh, o, bl + g * 1024);
+            }
         }
     }
 };
@@ -59,6 +76,18 @@ __device__ __forceinline__ void acc_to_bfrag(const float (&p)[16], bf16x8 (&f)[2
             f[c2][e] = pb[0];
             f[c2][e + 1] = pb[1];
         }
+}
+
+// accumulator rows 8r + 4h + 0..3  <-  vec[row0 + 8r + 4h + 0..3]   (r = 0..3)
+__device__ __forceinline__ void acc_init_rows(f32x16& acc, const float* vec, int row0, int h) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const f32x4 g4 = *reinterpret_cast<const f32x4*>(vec + row0 + 8 * r + 4 * h);
+        acc[4 * r] = g4[0];
+        acc[4 * r + 1] = g4[1];
+        acc[4 * r + 2] = g4[2];
+        acc[4 * r + 3] = g4[3];
+    }
 }
 
 }  // namespace gfwa
