@@ -32,7 +32,13 @@ def main() -> int:
     ap.add_argument("--workload", default="long_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=8)
-    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
+    ap.add_argument("--traffic-file", default=None,
+                    help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: lines "
+                         "'<kernel> <fetch bytes per launch> <write bytes per launch>', '#' comments "
+                         "(default: profiles/hbm_traffic_<workload>.txt)")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="before the warm-up, copy this many MiB once with a plain elementwise copy "
+                         "kernel (the known-size reference the traffic counters are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no inter-GPU part); "
@@ -73,6 +79,14 @@ def main() -> int:
         if wl.backward:
             g.gfwa_backward(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ, dK=dK, dV=dV, dalpha=dalpha)
 
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -111,12 +125,14 @@ def main() -> int:
         kernels[name] = {"avg_ms": round(avg_ms, 5), "launches": cnt, "bound": bound, "achieved": round(ach, 2),
                          "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    # measured HBM bytes per launch (fetch + write) of the dominant kernel, from the counter runs
     traffic = None
-    if os.path.exists(args.traffic_json):
-        try:
-            traffic = json.load(open(args.traffic_json)).get(args.workload, {}).get(dominant)
-        except Exception:
-            traffic = None
+    tfile = args.traffic_file or os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            f = line.split("#")[0].split()
+            if len(f) == 3 and f[0] == dominant:
+                traffic = float(f[1]) + float(f[2])
     roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
                 "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
                 "frac": kernels[dominant]["frac"], "traffic": traffic}
