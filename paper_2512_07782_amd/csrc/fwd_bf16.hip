@@ -1,11 +1,11 @@
 // GatedFWA fused forward for bf16 storage on gfx950 (paper Alg. 2, re-designed for CDNA4).
 //
-// One workgroup (4 waves, two workgroups per CU so that every SIMD always has a second wave to
-// issue from) owns a tile of 128 consecutive queries of one (b,h); a wave owns 32 of them.
-// Key/value tiles of 64 keys travel global -> LDS by direct loads (no staging registers, no LDS
-// stores), double buffered, and only the tiles that intersect the band [q0-w+1, q0+127] are
-// visited; inside a tile every wave skips the 32-key blocks that lie wholly outside the band of
-// its own queries, and masks only the blocks the band edge or the diagonal cuts.
+// One workgroup of 8 waves per CU owns a tile of 256 consecutive queries of one (b,h); a wave owns
+// 32 of them.  Key/value tiles of 64 keys travel global -> LDS by direct loads (no staging
+// registers, no LDS stores) through a ring of kRing buffers, and only the tiles that intersect the
+// band [q0-w+1, q0+255] are visited; inside a tile every wave skips the 32-key blocks that lie
+// wholly outside the band of its own queries, and masks only the blocks the band edge or the
+// diagonal cuts.
 //
 // The products are formed transposed so that a lane owns one query:
 //   S^T[key][query]  = g[key] + K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
@@ -14,48 +14,72 @@
 // so the row max / row sum of the online softmax are in-lane plus one exchange between the two
 // halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.
 //
+// Two-phase schedule.  The work of a wave on 32-key block n is split into a matrix phase
+//   M(n):  S_n = g + K_n Q^T   and   O += V_{n-1}^T P_{n-1}        (16 MFMAs at d = 128)
+// and a vector phase
+//   X(n):  P_n = exp2(S_n * sl - m * sl), running max / sum        (no MFMA)
+// separated by workgroup barriers.  The two waves that share a SIMD belong to different groups
+// (waves 0-3 and 4-7), and the second group runs one phase behind the first, so on every SIMD one
+// wave issues MFMAs while the other does the softmax arithmetic: the matrix pipe, the vector ALU
+// and the LDS are busy at the same time instead of all waves queueing for the same unit.
+//
 // The gate bias rides in the MFMA accumulator: S is initialised with g_i = (c_i - c_base) / scale
 // straight from LDS before the K Q^T chain, so S = q.k + g_i and the probability is one fused
-// multiply-add plus one exp2:  p = exp2(S*sl - m*sl), sl = scale * log2(e).  The per-query term
-// -(c_t - c_base) is constant along a row, cancels in the softmax, and is applied only to L.
-// c_base = c at the first query of the tile keeps the fp32 differences window-local.  The row sum
-// is taken over the bf16-rounded probabilities (one packed dot-product per pair), i.e. over exactly
-// the values that enter the PV product.  The running max is raised only when it grows by more than
-// 2^8, so most blocks need no rescale of O.
+// multiply-add plus one exp2, sl = scale * log2(e).  The per-query term -(c_t - c_base) is
+// constant along a row, cancels in the softmax, and is applied only to L.  c_base = c at the first
+// query of the tile keeps the fp32 differences window-local.  The row sum is taken over the
+// bf16-rounded probabilities (one packed dot-product per pair), i.e. over exactly the values that
+// enter the PV product.  The running max is raised only when it grows by more than 2^8, so most
+// blocks need no rescale of O.
+#include <cstddef>
+#include <type_traits>
+
 #include "gfwa_device.h"
 #include "gfwa_internal.h"
+#include "tile_stage.h"
 
 namespace gfwa {
 
-constexpr int kFwdThreads = 256;
-constexpr int kBC = 64;  // keys per LDS tile
+constexpr int kFwdWaves = 8;
+constexpr int kFwdThreads = 64 * kFwdWaves;
+constexpr int kFwdBR = 32 * kFwdWaves;  // queries per workgroup
+constexpr int kRing = 3;                // K/V tile buffers in flight
 
 template <int D>
 struct FwdSmem {
-    alignas(16) char k[2][kBC * D * 2];
-    alignas(16) char v[2][kBC * D * 2];
-    alignas(16) float g[2][kBC];  // (c - c_base) / scale
+    alignas(16) char k[kRing][kTileRows * D * 2];
+    alignas(16) char v[kRing][kTileRows * D * 2];
+    alignas(16) float craw[kRing][kTileRows];  // c of the tile's keys as loaded
+    alignas(16) float g[kRing][kTileRows];     // (c - c_base) / scale
 };
+
+// Phase boundary: all LDS traffic of this wave has completed, nothing is scheduled across it, and
+// (unlike __syncthreads) outstanding global->LDS loads stay in flight.
+__device__ __forceinline__ void wg_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 template <int D>
 __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ c, bf16_t* __restrict__ O, float* __restrict__ L, int N, int w,
     float scale_log2, int num_qtiles, int total_tiles) {
-    constexpr int BR = 128;
+    constexpr int BR = kFwdBR;
     constexpr int KC = D / 16;  // MFMA k-chunks along the head dimension
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
-    constexpr int kRowBytes = D * 2;
-    constexpr int kRowsPerLoad = 1024 / kRowBytes;    // rows one 1 KB global->LDS load covers
-    constexpr int kChunksPerRow = kRowBytes / 16;
-    constexpr int kLoadsPerWave = 16 / kRowsPerLoad;  // a wave fills 16 of the 64 rows of a tile
-    __shared__ FwdSmem<D> sm;
+    using Loader = TilePairLoader<D, kFwdWaves>;
+    constexpr int kBatch = Loader::kLoadsPerTilePair + 1;  // loads one wave issues per tile (K, V, c)
+    extern __shared__ __align__(16) char smem_raw[];
+    FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
     const int tile = xcd_remap(blockIdx.x, total_tiles);
     const int bh = tile / num_qtiles;
     const int q0 = (tile % num_qtiles) * BR;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wv >> 2;  // waves wv and wv + 4 share a SIMD and run in opposite phases
     const int h = lane >> 5, lq = lane & 31;
     const float sl = scale_log2;
     const float inv_scale = kLog2e / scale_log2;
@@ -67,7 +91,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const float* ch = c + (size_t)bh * N;
     const float cbase = ch[q0];
 
-    const int qw0 = q0 + wv * 32;  // first query of this wave
+    // the two waves of a SIMD take adjacent 32-query slabs, so their bands differ by one block
+    const int qw0 = q0 + 64 * (wv & 3) + 32 * grp;  // first query of this wave
     const int t = qw0 + lq;
 
     // Q^T fragments (B operand), resident for the whole tile loop (rows past N read row N-1)
@@ -82,43 +107,24 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
     const int k_lo = max(0, q0 - w + 1);
     const int k_hi = min(N, q0 + BR) - 1;
-    const int j_lo = k_lo / kBC, j_hi = k_hi / kBC;
-    const int jfull = N / kBC;  // tiles below jfull have all 64 rows inside the sequence
+    const int j_lo = k_lo / kTileRows, j_hi = k_hi / kTileRows;
+    const int ntiles = j_hi - j_lo + 1;
+    const int jfull = N / kTileRows;  // tiles below jfull have all 64 rows inside the sequence
 
-    // global -> LDS: wave wv fills rows 16wv..16wv+15 of a tile; lane p of a load writes row p /
-    // chunks-per-row of its group at physical chunk p % chunks-per-row and therefore fetches the
-    // logical chunk the swizzle maps there (the swizzle is an involution)
-    unsigned dma_off[kLoadsPerWave];
-#pragma unroll
-    for (int g = 0; g < kLoadsPerWave; ++g) {
-        const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
-        dma_off[g] = (unsigned)(row * kRowBytes + swz_chunk<D>(row, lane % kChunksPerRow) * 16);
-    }
-    auto load_tile = [&](int j, int buf) {
-        char* kl = sm.k[buf] + 16 * wv * kRowBytes;
-        char* vl = sm.v[buf] + 16 * wv * kRowBytes;
-        if (j < jfull) {
-            const size_t toff = (size_t)j * (kBC * kRowBytes);
-#pragma unroll
-            for (int g = 0; g < kLoadsPerWave; ++g) {
-                dma16(Kh + toff, dma_off[g], kl + g * 1024);
-                dma16(Vh + toff, dma_off[g], vl + g * 1024);
-            }
-        } else {  // ragged last tile: rows past N read row N-1 (finite; masked by causality)
-#pragma unroll
-            for (int g = 0; g < kLoadsPerWave; ++g) {
-                const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
-                const int key = min(j * kBC + row, N - 1);
-                const unsigned off =
-                    (unsigned)key * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, lane % kChunksPerRow) * 16);
-                dma16(Kh, off, kl + g * 1024);
-                dma16(Vh, off, vl + g * 1024);
-            }
-        }
+    Loader loader;
+    loader.init(wv, lane);
+    // every wave issues the same kBatch loads per tile, so the vmcnt bookkeeping is uniform; the
+    // 64 c values are fetched by all waves to the same place (identical data)
+    // Tiles are visited from the diagonal backwards: the gate bias only falls with distance, so
+    // the first blocks set the running max and later ones hardly ever force a rescale of O.
+    auto issue_tile = [&](int T) {  // T = position in visiting order, tile j_hi - T
+        const int j = j_hi - T, buf = T % kRing;
+        dma4(ch, (unsigned)min(j * kTileRows + lane, N - 1) * 4u, sm.craw[buf]);
+        loader.load(Kh, Vh, j, jfull, N, sm.k[buf], sm.v[buf]);
     };
-    auto gate_of = [&](int j) {  // this thread's g value of tile j (threads 0..63)
-        const int key = min(j * kBC + tid, N - 1);
-        return (ch[key] - cbase) * inv_scale;
+    auto publish_gate = [&](int T) {  // wave 0: raw c it loaded itself -> accumulator initial values
+        const int buf = T % kRing;
+        sm.g[buf][lane] = (sm.craw[buf][lane] - cbase) * inv_scale;
     };
 
     f32x16 o[DB];
@@ -128,42 +134,118 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
     float m = kNegBig, l = 0.0f;
 
-    load_tile(j_lo, 0);
-    if (tid < kBC) sm.g[0][tid] = gate_of(j_lo);
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
+    // the first step multiplies pf = 0 with the first half of the last ring slot: make it finite
+    if (tid * 16 < 32 * D * 2)
+        *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + tid * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
     __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    if (wv == 0) {
+        publish_gate(0);
+        if (ntiles > 1) publish_gate(1);
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    }
+    wg_barrier();
+    if (grp == 1) wg_barrier();  // second group: one phase behind
 
-    for (int j = j_lo; j <= j_hi; ++j) {
-        const int buf = (j - j_lo) & 1;
-        float g_next = 0.f;
-        if (j < j_hi) {
-            load_tile(j + 1, buf ^ 1);
-            if (tid < kBC) g_next = gate_of(j + 1);
+    // per-lane LDS byte offsets of the operand fragments inside ring slot 0; ring slot, 32-key
+    // block and 16-row group are compile-time displacements on top (the swizzle has period 16 rows)
+    typedef __attribute__((address_space(3))) const char* lds_ptr;
+    lds_ptr kaddr[KC], vaddr[DB][2], gaddr;
+    {
+        lds_ptr base = (lds_ptr)smem_raw;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+            kaddr[kc] = base + offsetof(FwdSmem<D>, k) + tile_off<D>(lane & 31, 2 * kc + h);
+        const int i16 = lane & 15;
+        const int row = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int col = 32 * db + 16 * ((lane & 31) >> 4) + 4 * (i16 & 3);
+            vaddr[db][0] = base + offsetof(FwdSmem<D>, v) + tile_off<D>(row, col >> 3) + (col & 7) * 2;
+            vaddr[db][1] = base + offsetof(FwdSmem<D>, v) + tile_off<D>(row + 8, col >> 3) + (col & 7) * 2;
         }
-
-        const char* kt = sm.k[buf];
-        const char* vt = sm.v[buf];
+        gaddr = base + offsetof(FwdSmem<D>, g) + 16 * h;
+    }
+    constexpr int kTileBytes = kTileRows * D * 2;
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    auto read_k = [&](int kc, int disp) -> bf16x8 {
+        return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(kaddr[kc] + disp);
+    };
+    auto read_vt = [&](int db, int disp) -> bf16x8 {
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vaddr[db][0] + disp));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vaddr[db][1] + disp));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto read_g = [&](f32x16& acc, int disp) {
 #pragma unroll
-        for (int sb = 0; sb < kBC / 32; ++sb) {
-            const int kb0 = j * kBC + 32 * sb;
-            // classify this 32-key block against the 32 queries of the wave
-            const bool act = (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
-            if (!act) continue;
-            const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 g4 = *reinterpret_cast<__attribute__((address_space(3))) const f32x4*>(gaddr + disp + 32 * r);
+            acc[4 * r] = g4[0];
+            acc[4 * r + 1] = g4[1];
+            acc[4 * r + 2] = g4[2];
+            acc[4 * r + 3] = g4[3];
+        }
+    };
 
-            // ---- S^T = g + K Q^T  (accumulator rows 8r + 4h + 0..3 <- g[32 sb + 8r + 4h + 0..3])
-            f32x16 s;
+    f32x16 s;
+    bf16x8 pf[2];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const f32x4 g4 = *reinterpret_cast<const f32x4*>(&sm.g[buf][32 * sb + 8 * r + 4 * h]);
-                s[4 * r] = g4[0];
-                s[4 * r + 1] = g4[1];
-                s[4 * r + 2] = g4[2];
-                s[4 * r + 3] = g4[3];
+    for (int e = 0; e < 8; ++e) pf[0][e] = pf[1][e] = (bf16_t)0.0f;
+    bool act_prev = false;  // block n-1 produced a P that still has to be multiplied into O
+
+    // one 32-key block step; ring slot and block-in-tile are compile-time so that every LDS
+    // address is a loop-invariant register plus an immediate
+    auto step = [&](auto buf_c, auto sb_c, int T) {
+        constexpr int buf = decltype(buf_c)::value;
+        constexpr int sb = decltype(sb_c)::value;
+        constexpr int half = 1 - sb;  // the upper 32 keys of a tile come first
+        constexpr int kdisp = buf * kTileBytes + 32 * half * (D * 2);
+        // block n-1: upper half of this tile, or lower half of the previous ring slot
+        constexpr int vdisp = sb ? buf * kTileBytes + 32 * (D * 2) : ((buf + kRing - 1) % kRing) * kTileBytes;
+        constexpr int gdisp = buf * (kTileRows * 4) + 32 * half * 4;
+        const int kb0 = (j_hi - T) * kTileRows + 32 * half;
+        const bool act = (T < ntiles) && (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
+        const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
+        // the buffer tile T+2 goes to was last read in M(2T) (PV of the block before this tile)
+        const bool issue = (sb == 1) && (T + 2 < ntiles);
+        if (issue) issue_tile(T + 2);
+
+        // ---------------- matrix phase M(n): one straight-line body.  A wave whose block n is
+        // outside its band still forms S (never looked at); a wave with no pending P multiplies
+        // V by pf = 0.  Only a wave with neither skips the phase.
+        if (act || act_prev) {
+            constexpr int kAhead = 4, NF = KC + 2 * DB;
+            bf16x8 fr[NF];  // fragment f: K chunk f for f < KC, else V^T fragment f - KC
+            auto fetch = [&](int f) {
+                if (f < KC) fr[f] = read_k(f, kdisp);
+                else fr[f] = read_vt((f - KC) % DB, vdisp + ((f - KC) / DB) * 16 * (D * 2));
+            };
+            read_g(s, gdisp);
+#pragma unroll
+            for (int f = 0; f < kAhead; ++f) fetch(f);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4 + kAhead, 0);
+#pragma unroll
+            for (int i = 0; i < NF; ++i) {
+                if (i < KC) s = mfma32(fr[i], qf[i], s);
+                else o[(i - KC) % DB] = mfma32(fr[i], pf[(i - KC) / DB], o[(i - KC) % DB]);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i + kAhead < NF) {
+                    fetch(i + kAhead);
+                    if (i + kAhead < KC) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                }
             }
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(kt, 32 * sb, kc, lane), qf[kc], s);
+        }
+        // tile T+1 is first read by group 0 right after the second barrier of an odd step
+        if (sb == 1 && grp == 1) {
+            if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+        }
+        wg_barrier();
 
+        // ---------------- vector phase X(n)
+        if (act) {
             if (!full) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -193,29 +275,46 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                     for (int v = 0; v < 16; ++v) o[db][v] *= a;
             }
             const float nm = -m * sl;
-            bf16x8 pf[2];
-            const bf16x2 one2 = {(bf16_t)1.0f, (bf16_t)1.0f};
+            float l2 = 0.f;
 #pragma unroll
             for (int cc = 0; cc < 8; ++cc) {
                 f32x2 pr = {fast_exp2(fmaf(s[2 * cc], sl, nm)), fast_exp2(fmaf(s[2 * cc + 1], sl, nm))};
                 const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
-                l = __builtin_amdgcn_fdot2_f32_bf16(pb, one2, l, false);  // per-half partial row sum
+                // per-half partial row sum with plain adds: the packed dot-product instructions
+                // run on the matrix pipe and would stall behind the other wave's MFMAs
+                l += pr[0];
+                l2 += pr[1];
                 pf[cc >> 2][2 * (cc & 3)] = pb[0];
                 pf[cc >> 2][2 * (cc & 3) + 1] = pb[1];
             }
-
-            // ---- O^T += V^T P^T
+            l += l2;
+        } else {
 #pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    o[db] = mfma32(lds_read_tr_frag<D>(vt, 32 * sb + 16 * c2, db, lane), pf[c2], o[db]);
+            for (int e = 0; e < 8; ++e) pf[0][e] = pf[1][e] = (bf16_t)0.0f;
         }
-
-        if (j < j_hi && tid < kBC) sm.g[buf ^ 1][tid] = g_next;
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile j+1 has landed
-        __syncthreads();
+        act_prev = act;
+        if (sb == 1 && grp == 0) {
+            if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+            if (wv == 0 && T + 1 < ntiles && T >= 1) {  // tiles 0 and 1 were published in the prologue
+                publish_gate(T + 1);
+            }
+        }
+        wg_barrier();
+    };
+    auto tile_step = [&](auto buf_c, int T) {
+        step(buf_c, std::integral_constant<int, 0>{}, T);
+        if (T < ntiles) step(buf_c, std::integral_constant<int, 1>{}, T);  // T = ntiles: drain only
+    };
+    static_assert(kRing == 3, "the tile loop is unrolled over the ring");
+    for (int T = 0; T <= ntiles; T += 3) {
+        tile_step(std::integral_constant<int, 0>{}, T);
+        if (T + 1 > ntiles) break;
+        tile_step(std::integral_constant<int, 1>{}, T + 1);
+        if (T + 2 > ntiles) break;
+        tile_step(std::integral_constant<int, 2>{}, T + 2);
     }
+    if (grp == 0) wg_barrier();  // matches the extra barrier the second group started with
 
     // ---- epilogue: O = O^T / l, L = ln2 * (m*sl + log2 l) - (c_t - c_base)
     const float lt = xhalf_sum(l);  // the two halves of the wave hold complementary keys
@@ -237,13 +336,19 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 template <int D>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const float* c, void* O,
                              float* L, int B, int H, int N, int w, float scale, hipStream_t s) {
-    constexpr int BR = 128;
-    const int num_qtiles = (N + BR - 1) / BR;
+    const int num_qtiles = (N + kFwdBR - 1) / kFwdBR;
     const int total = B * H * num_qtiles;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_kernel<D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(FwdSmem<D>));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     ProfScope prof(kKernForward, s);
-    hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(total), dim3(kFwdThreads), 0, s, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w, scale * kLog2e, num_qtiles,
-                       total);
+    hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(total), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
+                       (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w,
+                       scale * kLog2e, num_qtiles, total);
     return hipGetLastError();
 }
 

@@ -15,16 +15,19 @@ struct TilePairSmem {
     alignas(16) char b[2][kTileRows * D * 2];
 };
 
-// Wave wv fills rows 16wv..16wv+15 of a tile with 1 KB loads; lane p of a load writes row
-// p / chunks-per-row of its group at physical chunk p % chunks-per-row and therefore fetches the
-// logical chunk the swizzle maps there (the swizzle is an involution).
-template <int D>
+// Each of the WAVES waves of the workgroup fills 64 / WAVES consecutive rows of a tile with 1 KB
+// loads; lane p of a load writes row p / chunks-per-row of its group at physical chunk
+// p % chunks-per-row and therefore fetches the logical chunk the swizzle maps there (the swizzle
+// is an involution).
+template <int D, int WAVES = 4>
 struct TilePairLoader {
     static constexpr int kRowBytes = D * 2;
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;
     static constexpr int kChunksPerRow = kRowBytes / 16;
-    static constexpr int kLoadsPerWave = 16 / kRowsPerLoad;
+    static constexpr int kRowsPerWave = kTileRows / WAVES;
+    static constexpr int kLoadsPerWave = kRowsPerWave / kRowsPerLoad;
     static constexpr int kLoadsPerTilePair = 2 * kLoadsPerWave;  // per wave
+    static_assert(kLoadsPerWave >= 1, "a wave must cover at least one 1 KB load");
     unsigned off[kLoadsPerWave];
     int wv, lane;
 
@@ -33,16 +36,16 @@ struct TilePairLoader {
         lane = lane_;
 #pragma unroll
         for (int g = 0; g < kLoadsPerWave; ++g) {
-            const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
+            const int row = kRowsPerWave * wv + kRowsPerLoad * g + lane / kChunksPerRow;
             off[g] = (unsigned)(row * kRowBytes + swz_chunk<D>(row, lane % kChunksPerRow) * 16);
         }
     }
     // tile index j (rows 64j .. 64j+63) of the [N, D] matrices at Ah and Bh into buffer `buf`;
     // tiles below jfull = N / 64 lie wholly inside the sequence
     __device__ __forceinline__ void load(const char* Ah, const char* Bh, int j, int jfull, int N,
-                                         TilePairSmem<D>& sm, int buf) const {
-        char* al = sm.a[buf] + 16 * wv * kRowBytes;
-        char* bl = sm.b[buf] + 16 * wv * kRowBytes;
+                                         char* a_tile, char* b_tile) const {
+        char* al = a_tile + kRowsPerWave * wv * kRowBytes;
+        char* bl = b_tile + kRowsPerWave * wv * kRowBytes;
         if (j < jfull) {
             const size_t toff = (size_t)j * (kTileRows * kRowBytes);
 #pragma unroll
@@ -53,7 +56,7 @@ struct TilePairLoader {
         } else {
 #pragma unroll
             for (int g = 0; g < kLoadsPerWave; ++g) {
-                const int row = 16 * wv + kRowsPerLoad * g + lane / kChunksPerRow;
+                const int row = kRowsPerWave * wv + kRowsPerLoad * g + lane / kChunksPerRow;
                 const int r = min(j * kTileRows + row, N - 1);
                 const unsigned o =
                     (unsigned)r * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, lane % kChunksPerRow) * 16);
