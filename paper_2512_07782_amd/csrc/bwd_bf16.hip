@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
             sm.dvec[buf][tid] = d_stage;
         }
     };
-    loader.load(Qh, Gh, i_lo, ifull, N, sm.qg, 0);
+    loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
     load_vec(i_lo);
     store_vec(0);
     __builtin_amdgcn_s_waitcnt(0);
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     for (int i = i_lo; i <= i_hi; ++i) {
         const int buf = (i - i_lo) & 1;
         if (i < i_hi) {
-            loader.load(Qh, Gh, i + 1, ifull, N, sm.qg, buf ^ 1);
+            loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
             load_vec(i + 1);
         }
         const char* qt = sm.qg.a[buf];
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
         const int key = min(j * kTileRows + tid, N - 1);
         return (ch[key] - cbase) * inv_scale;
     };
-    loader.load(Kh, Vh, j_lo, jfull, N, sm.kv, 0);
+    loader.load(Kh, Vh, j_lo, jfull, N, sm.kv.a[0], sm.kv.b[0]);
     if (tid < kTileRows) sm.g[0][tid] = gate_of(j_lo);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
         const int buf = (j - j_lo) & 1;
         float g_next = 0.f;
         if (j < j_hi) {
-            loader.load(Kh, Vh, j + 1, jfull, N, sm.kv, buf ^ 1);
+            loader.load(Kh, Vh, j + 1, jfull, N, sm.kv.a[buf ^ 1], sm.kv.b[buf ^ 1]);
             if (tid < kTileRows) g_next = gate_of(j + 1);
         }
         const char* kt = sm.kv.a[buf];

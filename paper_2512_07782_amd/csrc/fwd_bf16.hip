@@ -14,10 +14,11 @@
 // so the row max / row sum of the online softmax are in-lane plus one exchange between the two
 // halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.
 //
-// Two-phase schedule.  The work of a wave on 32-key block n is split into a matrix phase
-//   M(n):  S_n = g + K_n Q^T   and   O += V_{n-1}^T P_{n-1}        (16 MFMAs at d = 128)
+// Two-phase schedule.  The work of a wave on key tile T (two 32-key blocks) is split into a
+// matrix phase
+//   M(T):  S_T = g + K_T Q^T   and   O += V_{T-1}^T P_{T-1}        (32 MFMAs at d = 128)
 // and a vector phase
-//   X(n):  P_n = exp2(S_n * sl - m * sl), running max / sum        (no MFMA)
+//   X(T):  P_T = exp2(S_T * sl - m * sl), row sums                 (no MFMA)
 // separated by workgroup barriers.  The two waves that share a SIMD belong to different groups
 // (waves 0-3 and 4-7), and the second group runs one phase behind the first, so on every SIMD one
 // wave issues MFMAs while the other does the softmax arithmetic: the matrix pipe, the vector ALU
@@ -29,8 +30,14 @@
 // constant along a row, cancels in the softmax, and is applied only to L.  c_base = c at the first
 // query of the tile keeps the fp32 differences window-local.  The row sum is taken over the
 // bf16-rounded probabilities (one packed dot-product per pair), i.e. over exactly the values that
-// enter the PV product.  The running max is raised only when it grows by more than 2^8, so most
-// blocks need no rescale of O.
+// enter the PV product.
+//
+// Deferred running max.  exp2 is taken against the reference exponent m left by earlier tiles
+// without first looking for the tile's own maximum; fp32 and bf16 share their exponent range, so a
+// probability may grow to 2^60 with no loss of precision.  Only when a lane's tile sum exceeds that
+// (always on a wave's first tile, where m is still "minus infinity") does the wave take the slow
+// path: find the true maximum, raise m, rescale O and l, and redo the exponentials.  Tiles are
+// visited from the diagonal backwards, where the gate bias is largest, so this is rare.
 #include <cstddef>
 #include <type_traits>
 
@@ -43,7 +50,7 @@ namespace gfwa {
 constexpr int kFwdWaves = 8;
 constexpr int kFwdThreads = 64 * kFwdWaves;
 constexpr int kFwdBR = 32 * kFwdWaves;  // queries per workgroup
-constexpr int kRing = 3;                // K/V tile buffers in flight
+constexpr int kRing = 4;                // K/V tile slots: read for PV, read for S, two in flight
 
 template <int D>
 struct FwdSmem {
@@ -83,7 +90,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const int h = lane >> 5, lq = lane & 31;
     const float sl = scale_log2;
     const float inv_scale = kLog2e / scale_log2;
-    const float thr = 8.0f / scale_log2;  // growth of the running max (raw units) that forces a rescale
 
     const size_t head_off = (size_t)bh * N * D;
     const char* Kh = reinterpret_cast<const char*>(K + head_off);
@@ -136,9 +142,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
-    // the first step multiplies pf = 0 with the first half of the last ring slot: make it finite
-    if (tid * 16 < 32 * D * 2)
-        *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + tid * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the first step multiplies pf = 0 with the last ring slot: make it finite
+    for (int o16 = tid * 16; o16 < kTileRows * D * 2; o16 += kFwdThreads * 16)
+        *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + o16) = f32x4{0.f, 0.f, 0.f, 0.f};
     __builtin_amdgcn_s_waitcnt(0);
     if (wv == 0) {
         publish_gate(0);
@@ -188,84 +194,124 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         }
     };
 
-    f32x16 s;
-    bf16x8 pf[2];
+    f32x16 s[2];     // S^T of the two blocks of the current tile (0: upper 32 keys, 1: lower)
+    bf16x8 pf[2][2];  // their probabilities as B operands
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf[0][e] = pf[1][e] = (bf16_t)0.0f;
-    bool act_prev = false;  // block n-1 produced a P that still has to be multiplied into O
+    for (int e = 0; e < 8; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = (bf16_t)0.0f;
+    bool pending = false;  // the previous tile left a P that still has to be multiplied into O
+    constexpr float kBig = 1.152921504606846976e18f;  // 2^60
 
-    // one 32-key block step; ring slot and block-in-tile are compile-time so that every LDS
-    // address is a loop-invariant register plus an immediate
-    auto step = [&](auto buf_c, auto sb_c, int T) {
+    // one key tile; the ring slot is a compile-time constant so that every LDS address is a
+    // loop-invariant register plus an immediate.  Block 0 is the upper half of the tile.
+    auto tile_step = [&](auto buf_c, int T) {
         constexpr int buf = decltype(buf_c)::value;
-        constexpr int sb = decltype(sb_c)::value;
-        constexpr int half = 1 - sb;  // the upper 32 keys of a tile come first
-        constexpr int kdisp = buf * kTileBytes + 32 * half * (D * 2);
-        // block n-1: upper half of this tile, or lower half of the previous ring slot
-        constexpr int vdisp = sb ? buf * kTileBytes + 32 * (D * 2) : ((buf + kRing - 1) % kRing) * kTileBytes;
-        constexpr int gdisp = buf * (kTileRows * 4) + 32 * half * 4;
-        const int kb0 = (j_hi - T) * kTileRows + 32 * half;
-        const bool act = (T < ntiles) && (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
-        const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
-        // the buffer tile T+2 goes to was last read in M(2T) (PV of the block before this tile)
-        const bool issue = (sb == 1) && (T + 2 < ntiles);
+        constexpr int pbuf = (buf + kRing - 1) % kRing;  // slot of the previous tile
+        const int kt0 = (j_hi - T) * kTileRows;
+        bool act[2], full[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int kb0 = kt0 + 32 * (1 - b);
+            act[b] = (T < ntiles) && (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
+            full[b] = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
+        }
+        const bool any_act = act[0] || act[1];
+        // slot (T+2) % kRing held tile T-2, whose V was last read in M(T-1)
+        const bool issue = T + 2 < ntiles;
         if (issue) issue_tile(T + 2);
 
-        // ---------------- matrix phase M(n): one straight-line body.  A wave whose block n is
-        // outside its band still forms S (never looked at); a wave with no pending P multiplies
-        // V by pf = 0.  Only a wave with neither skips the phase.
-        if (act || act_prev) {
-            constexpr int kAhead = 4, NF = KC + 2 * DB;
-            bf16x8 fr[NF];  // fragment f: K chunk f for f < KC, else V^T fragment f - KC
+        // ---------------- matrix phase M(T): one straight-line body.  A block outside the band
+        // of this wave still gets its S formed (never looked at); a wave with no pending P
+        // multiplies V by pf = 0.  Only a wave with neither skips the phase.
+        if (any_act || pending) {
+            constexpr int kAhead = 4, NS = 2 * KC, NP = 4 * DB, NF = NS + NP;
+            bf16x8 fr[NF];  // fragment f: K chunk of block f / KC for f < NS, else V^T fragment
             auto fetch = [&](int f) {
-                if (f < KC) fr[f] = read_k(f, kdisp);
-                else fr[f] = read_vt((f - KC) % DB, vdisp + ((f - KC) / DB) * 16 * (D * 2));
+                if (f < NS) {
+                    fr[f] = read_k(f % KC, buf * kTileBytes + 32 * (1 - f / KC) * (D * 2));
+                } else {
+                    const int g = f - NS, b = g / (2 * DB), c2 = (g / DB) % 2, db = g % DB;
+                    fr[f] = read_vt(db, pbuf * kTileBytes + (32 * (1 - b) + 16 * c2) * (D * 2));
+                }
             };
-            read_g(s, gdisp);
+            read_g(s[0], buf * (kTileRows * 4) + 32 * 4);
+            read_g(s[1], buf * (kTileRows * 4));
 #pragma unroll
             for (int f = 0; f < kAhead; ++f) fetch(f);
-            __builtin_amdgcn_sched_group_barrier(0x100, 4 + kAhead, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 8 + kAhead, 0);
 #pragma unroll
             for (int i = 0; i < NF; ++i) {
-                if (i < KC) s = mfma32(fr[i], qf[i], s);
-                else o[(i - KC) % DB] = mfma32(fr[i], pf[(i - KC) / DB], o[(i - KC) % DB]);
+                if (i < NS) {
+                    s[i / KC] = mfma32(fr[i], qf[i % KC], s[i / KC]);
+                } else {
+                    const int g = i - NS, b = g / (2 * DB), c2 = (g / DB) % 2, db = g % DB;
+                    o[db] = mfma32(fr[i], pf[b][c2], o[db]);
+                }
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (i + kAhead < NF) {
                     fetch(i + kAhead);
-                    if (i + kAhead < KC) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (i + kAhead < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                 }
             }
         }
-        // tile T+1 is first read by group 0 right after the second barrier of an odd step
-        if (sb == 1 && grp == 1) {
+        // tile T+1 is first read by group 0 right after the second barrier of this step
+        if (grp == 1) {
             if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
             else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
         }
         wg_barrier();
 
-        // ---------------- vector phase X(n)
-        if (act) {
-            if (!full) {
+        // ---------------- vector phase X(T)
+        if (any_act) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int i = kb0 + acc_row(v, h);
-                    const bool keep = (i <= t) && (i > t - w);
-                    s[v] = keep ? s[v] : -INFINITY;
+            for (int b = 0; b < 2; ++b) {
+                if (act[b] && !full[b]) {
+                    const int kb0 = kt0 + 32 * (1 - b);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int i = kb0 + acc_row(v, h);
+                        const bool keep = (i <= t) && (i > t - w);
+                        s[b][v] = keep ? s[b][v] : -INFINITY;
+                    }
                 }
             }
-            float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
-            float mx2 = fmaxf(fmaxf(s[8], s[9]), s[10]);
-            mx = fmaxf(fmaxf(mx, s[3]), s[4]);
-            mx2 = fmaxf(fmaxf(mx2, s[11]), s[12]);
-            mx = fmaxf(fmaxf(mx, s[5]), s[6]);
-            mx2 = fmaxf(fmaxf(mx2, s[13]), s[14]);
-            mx = xhalf_max(fmaxf(fmaxf(mx, s[7]), fmaxf(mx2, s[15])));
-            // Raise the running max only when it grows by more than 2^8: p stays <= 256, which
-            // bf16 holds as well as any other magnitude, and most blocks need no rescale.
-            const bool grow = mx > m + thr;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float mnew = grow ? mx : m;
+            float tsum;
+            auto exponentiate = [&]() {
+                const float nm = -m * sl;
+                float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    if (act[b]) {
+#pragma unroll
+                        for (int cc = 0; cc < 8; ++cc) {
+                            f32x2 pr = {fast_exp2(fmaf(s[b][2 * cc], sl, nm)), fast_exp2(fmaf(s[b][2 * cc + 1], sl, nm))};
+                            const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
+                            // plain adds: the packed dot-product instructions run on the matrix
+                            // pipe and would stall behind the other wave's MFMAs
+                            part[2 * b] += pr[0];
+                            part[2 * b + 1] += pr[1];
+                            pf[b][cc >> 2][2 * (cc & 3)] = pb[0];
+                            pf[b][cc >> 2][2 * (cc & 3) + 1] = pb[1];
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) pf[b][0][e] = pf[b][1][e] = (bf16_t)0.0f;
+                    }
+                }
+                tsum = (part[0] + part[1]) + (part[2] + part[3]);
+            };
+            exponentiate();
+            if (__builtin_amdgcn_ballot_w64(!(tsum <= kBig)) != 0) {
+                // slow path: true maximum of the tile, common to the two halves of the wave
+                float mx = -INFINITY;
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    if (act[b]) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[b][v]);
+                    }
+                mx = xhalf_max(mx);
+                const float mnew = fmaxf(m, mx);
                 const float a = fast_exp2((m - mnew) * sl);
                 m = mnew;
                 l *= a;
@@ -273,46 +319,31 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[db][v] *= a;
+                exponentiate();
             }
-            const float nm = -m * sl;
-            float l2 = 0.f;
-#pragma unroll
-            for (int cc = 0; cc < 8; ++cc) {
-                f32x2 pr = {fast_exp2(fmaf(s[2 * cc], sl, nm)), fast_exp2(fmaf(s[2 * cc + 1], sl, nm))};
-                const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
-                // per-half partial row sum with plain adds: the packed dot-product instructions
-                // run on the matrix pipe and would stall behind the other wave's MFMAs
-                l += pr[0];
-                l2 += pr[1];
-                pf[cc >> 2][2 * (cc & 3)] = pb[0];
-                pf[cc >> 2][2 * (cc & 3) + 1] = pb[1];
-            }
-            l += l2;
+            l += tsum;
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[0][e] = pf[1][e] = (bf16_t)0.0f;
+            for (int e = 0; e < 8; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = (bf16_t)0.0f;
         }
-        act_prev = act;
-        if (sb == 1 && grp == 0) {
+        pending = any_act;
+        if (grp == 0) {
             if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
             else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
-            if (wv == 0 && T + 1 < ntiles && T >= 1) {  // tiles 0 and 1 were published in the prologue
-                publish_gate(T + 1);
-            }
+            if (wv == 0 && T + 1 < ntiles && T >= 1) publish_gate(T + 1);  // tiles 0, 1: prologue
         }
         wg_barrier();
     };
-    auto tile_step = [&](auto buf_c, int T) {
-        step(buf_c, std::integral_constant<int, 0>{}, T);
-        if (T < ntiles) step(buf_c, std::integral_constant<int, 1>{}, T);  // T = ntiles: drain only
-    };
-    static_assert(kRing == 3, "the tile loop is unrolled over the ring");
-    for (int T = 0; T <= ntiles; T += 3) {
+    static_assert(kRing == 4, "the tile loop is unrolled over the ring");
+    // T = ntiles is the drain step (only the PV product of the last tile)
+    for (int T = 0; T <= ntiles; T += 4) {
         tile_step(std::integral_constant<int, 0>{}, T);
         if (T + 1 > ntiles) break;
         tile_step(std::integral_constant<int, 1>{}, T + 1);
         if (T + 2 > ntiles) break;
         tile_step(std::integral_constant<int, 2>{}, T + 2);
+        if (T + 3 > ntiles) break;
+        tile_step(std::integral_constant<int, 3>{}, T + 3);
     }
     if (grp == 0) wg_barrier();  // matches the extra barrier the second group started with
 
