@@ -195,9 +195,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     };
 
     f32x16 s[2];     // S^T of the two blocks of the current tile (0: upper 32 keys, 1: lower)
-    bf16x8 pf[2][2];  // their probabilities as B operands
+    u32x4 pf[2][2];  // their probabilities as B operands (bf16 pairs)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = (bf16_t)0.0f;
+    for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
     bool pending = false;  // the previous tile left a P that still has to be multiplied into O
     constexpr float kBig = 1.152921504606846976e18f;  // 2^60
 
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                     s[i / KC] = mfma32(fr[i], qf[i % KC], s[i / KC]);
                 } else {
                     const int g = i - NS, b = g / (2 * DB), c2 = (g / DB) % 2, db = g % DB;
-                    o[db] = mfma32(fr[i], pf[b][c2], o[db]);
+                    o[db] = mfma32(fr[i], __builtin_bit_cast(bf16x8, pf[b][c2]), o[db]);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (i + kAhead < NF) {
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                 }
             }
             float tsum;
-            auto exponentiate = [&]() {
+            auto exponentiate = [&]() __attribute__((always_inline)) {
                 const float nm = -m * sl;
                 float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -290,12 +290,11 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                             // pipe and would stall behind the other wave's MFMAs
                             part[2 * b] += pr[0];
                             part[2 * b + 1] += pr[1];
-                            pf[b][cc >> 2][2 * (cc & 3)] = pb[0];
-                            pf[b][cc >> 2][2 * (cc & 3) + 1] = pb[1];
+                            pf[b][cc >> 2][cc & 3] = __builtin_bit_cast(unsigned, pb);
                         }
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) pf[b][0][e] = pf[b][1][e] = (bf16_t)0.0f;
+                        for (int e = 0; e < 4; ++e) pf[b][0][e] = pf[b][1][e] = 0u;
                     }
                 }
                 tsum = (part[0] + part[1]) + (part[2] + part[3]);
@@ -324,7 +323,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
             l += tsum;
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = (bf16_t)0.0f;
+            for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
         }
         pending = any_act;
         if (grp == 0) {
