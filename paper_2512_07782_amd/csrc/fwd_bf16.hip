@@ -53,20 +53,7 @@ constexpr int kFwdBR = 32 * kFwdWaves;  // queries per workgroup
 constexpr int kRing = 4;                // K/V tile slots: read for PV, read for S, two in flight
 
 template <int D>
-struct FwdSmem {
-    alignas(16) char k[kRing][kTileRows * D * 2];
-    alignas(16) char v[kRing][kTileRows * D * 2];
-    alignas(16) float craw[kRing][kTileRows];  // c of the tile's keys as loaded
-    alignas(16) float g[kRing][kTileRows];     // (c - c_base) / scale
-};
-
-// Phase boundary: all LDS traffic of this wave has completed, nothing is scheduled across it, and
-// (unlike __syncthreads) outstanding global->LDS loads stay in flight.
-__device__ __forceinline__ void wg_barrier() {
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-}
+using FwdSmem = KvRingSmem<D, kRing>;
 
 template <int D>
 __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(

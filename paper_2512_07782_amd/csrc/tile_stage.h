@@ -67,6 +67,24 @@ struct TilePairLoader {
     }
 };
 
+// Ring of RING key tiles (K rows and V rows, swizzled) with the gate values of their keys, as
+// used by the kernels that stream keys past resident queries.
+template <int D, int RING>
+struct KvRingSmem {
+    alignas(16) char k[RING][kTileRows * D * 2];
+    alignas(16) char v[RING][kTileRows * D * 2];
+    alignas(16) float craw[RING][kTileRows];  // c of the tile's keys as loaded
+    alignas(16) float g[RING][kTileRows];     // (c - c_base) / scale
+};
+
+// Phase boundary of the two-phase kernels: all LDS traffic of this wave has completed, nothing is
+// scheduled across it, and (unlike __syncthreads) outstanding global->LDS loads stay in flight.
+__device__ __forceinline__ void wg_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // f32x16 accumulator -> two bf16 B-operand fragments (k-chunks of 16 rows each), in the row order
 // the accumulator already has.
 __device__ __forceinline__ void acc_to_bfrag(const float (&p)[16], bf16x8 (&f)[2]) {

@@ -7,8 +7,11 @@ Tolerances (stated target of the build):
            bf16 pipeline: probabilities enter the PV product rounded to bf16 (unit roundoff 2^-8)
            and O is stored in bf16, so |err| <= 2^-8 (sum_i P_ti |V_ix| + |O_tx|) elementwise (plus
            5% and 1e-3 for the fp32 steps), and the mean bar scales with the value scale, 3 * 2e-3.
-  bf16 L : |err| <= 2^-8 + 1e-4: the kernels sum the bf16-rounded probabilities (the denominator
-           that O actually uses), each within a factor 1 +- 2^-8 of the exact one.
+  bf16 L : the row sum is taken in fp32 over the unrounded probabilities, so L is an fp32
+           quantity: |err| <= 1e-4 + 1e-5 |L| + 2^-21 * span, where span is the largest difference
+           of c inside one workgroup's key range (window + 256 queries): the kernel forms
+           c_i - c_base, its quotient by the scale and the MFMA accumulation in fp32, a few
+           roundings at relative 2^-24 of a number as large as that span.
   fp32   : ||err||_inf / ||ref||_inf <= 1e-5.
   grads  : relative L2 error <= 1e-2 per tensor (bf16), <= 1e-5 (fp32).
 The forward entry point is compared with the oracle on the same fp32 prefix c (the oracle's
@@ -75,10 +78,15 @@ def test_gate_prefix(g, oracle, B, H, N):
 # ------------------------------------------------------------------------------------------
 # forward
 # ------------------------------------------------------------------------------------------
+LAST = {"c_span": 0.0}  # largest c difference inside a workgroup's key range, last run_forward
+
+
 def run_forward(g, oracle, wl, heads=None, want_bound=False):
     ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha")}
     c64 = oracle.gate_prefix(ins["alpha"])
     c32 = c64.astype(np.float32)
+    reach = min(wl.N - 1, wl.w + 256)
+    LAST["c_span"] = float((c64[..., reach:] - c64[..., :wl.N - reach]).max()) if reach > 0 else 0.0
     O, L = g.gfwa_forward(dev(ins["Q"], wl.dtype), dev(ins["K"], wl.dtype), dev(ins["V"], wl.dtype),
                           dev(c32, "f32"), wl.w, wl.scale)
     torch.cuda.synchronize()
@@ -124,9 +132,9 @@ def check_bf16_forward(O, L, O_ref, L_ref, bound=None, value_scale=1.0, tag=""):
     else:
         assert err.max() <= 2e-2
     assert err.mean() <= 2e-3 * value_scale
-    # L is the log of the row sum of the bf16-rounded probabilities that enter the PV product
-    # (unit roundoff 2^-8), so it can differ from the exact log-sum-exp by up to 2^-8
-    assert (lerr <= 2.0 ** -8 + 1e-4 + 1e-5 * np.abs(L_ref)).all()
+    # L comes from an fp32 row sum of unrounded probabilities; its error is that of the fp32
+    # exponent arithmetic on gate differences as large as the span of c in a workgroup's key range
+    assert (lerr <= 1e-4 + 1e-5 * np.abs(L_ref) + 2.0 ** -21 * LAST["c_span"]).all()
 
 
 SMALL_BF16 = [
