@@ -31,7 +31,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="long_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=8)
+    ap.add_argument("--cpu-heads", type=int, default=32)
     ap.add_argument("--traffic-file", default=None,
                     help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: lines "
                          "'<kernel> <fetch bytes per launch> <write bytes per launch>', '#' comments "
