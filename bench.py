@@ -109,7 +109,7 @@ def main() -> int:
         "forward": ("mfma", f_fwd),
         "bwd_rowdot": ("hbm", bhn * (4.0 * d + 4.0)),
         "bwd_dkv": ("mfma", 8.0 * bhn * w * d),     # S, dP, dV, dK products
-        "bwd_dq": ("mfma", 2.0 * bhn * w * d),      # the dQ product; its S and dP are recomputation
+        "bwd_dq": ("mfma", 2.0 * bhn * w * d),      # the dQ product; its S and dP are recomputation (bf16: also forms D)
         "gate_grad_scan": ("hbm", 12.0 * bhn),
     }
     kernels = {}
@@ -142,7 +142,7 @@ def main() -> int:
               "fwd_tflops_exact": round(wl.flops_fwd_exact() / fwd_ms / 1e9, 2),
               "fwd_frac_bf16_peak": round(f_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
     if wl.backward:
-        bwd_ms = sum(kernels[k]["avg_ms"] for k in ("bwd_rowdot", "bwd_dkv", "bwd_dq", "gate_grad_scan"))
+        bwd_ms = sum(kernels[k]["avg_ms"] for k in ("bwd_rowdot", "bwd_dkv", "bwd_dq", "gate_grad_scan") if k in kernels)
         detail.update({"bwd_ms": round(bwd_ms, 5), "bwd_tflops_nominal": round(f_bwd / bwd_ms / 1e9, 2),
                        "bwd_frac_bf16_peak": round(f_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)})
 
