@@ -279,6 +279,36 @@ def test_backward_bf16_full_size(g, oracle, name, heads):
     check_grads(got, ref, 1e-2, name)
 
 
+MID = [  # several 256-query workgroups, many key tiles, ragged ends; sampled heads
+    # B, H, N, d, w, heads
+    (1, 4, 4099, 64, 512, [0, 3]), (1, 2, 5003, 128, 3000, [1]), (2, 2, 2050, 128, 2050, [0, 3]),
+    (1, 2, 3001, 64, 7000, [1]),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,w,heads", MID)
+def test_forward_backward_bf16_mid_size(g, oracle, B, H, N, d, w, heads):
+    """Sizes between the small exhaustive cases and the benchmark workloads: multi-tile both ways,
+    N not a multiple of any tile, windows below, at and above N."""
+    note("mid size", B, H, N, d, w)
+    wl = gi.custom("mid", B, H, N, d, w, "bf16", alpha_mu=-1.5, index=14, backward=True)
+    O, L, O_ref, L_ref = run_forward(g, oracle, wl, heads=heads)
+    check_bf16_forward(O, L, O_ref, L_ref, tag="mid")
+    got, ref = run_backward(g, oracle, wl, heads=heads)
+    check_grads(got, ref, 1e-2, "mid")
+
+
+def test_forward_is_deterministic(g, oracle):
+    wl = gi.custom("detf", 1, 2, 1500, 128, 700, "bf16", alpha_mu=-1.0, index=15)
+    ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha")}
+    c = g.gfwa_gate_prefix(dev(ins["alpha"], "f32"))
+    args = [dev(ins[t], "bf16") for t in ("Q", "K", "V")]
+    O1, L1 = g.gfwa_forward(*args, c, wl.w, wl.scale)
+    O2, L2 = g.gfwa_forward(*args, c, wl.w, wl.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+
+
 def test_backward_is_deterministic(g, oracle):
     wl = gi.custom("det", 1, 2, 700, 128, 200, "bf16", alpha_mu=-1.0, index=13, backward=True)
     a, _ = run_backward(g, oracle, wl, chained=True)
