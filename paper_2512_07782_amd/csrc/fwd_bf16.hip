@@ -19,10 +19,11 @@
 //   M(T):  S_T = g + K_T Q^T   and   O += V_{T-1}^T P_{T-1}        (32 MFMAs at d = 128)
 // and a vector phase
 //   X(T):  P_T = exp2(S_T * sl - m * sl), row sums                 (no MFMA)
-// separated by workgroup barriers.  The two waves that share a SIMD belong to different groups
-// (waves 0-3 and 4-7), and the second group runs one phase behind the first, so on every SIMD one
-// wave issues MFMAs while the other does the softmax arithmetic: the matrix pipe, the vector ALU
-// and the LDS are busy at the same time instead of all waves queueing for the same unit.
+// The two waves that share a SIMD belong to different groups (waves 0-3 and 4-7).  There is one
+// workgroup barrier per key tile; the first group takes it after X(T), the second after M(T), so
+// the second group's vector phase runs next to the first group's next matrix phase: on every SIMD
+// one wave issues MFMAs while the other does the softmax arithmetic, instead of all waves queueing
+// for the same unit.
 //
 // The gate bias rides in the MFMA accumulator: S is initialised with g_i = (c_i - c_base) / scale
 // straight from LDS before the K Q^T chain, so S = q.k + g_i and the probability is one fused
@@ -139,7 +140,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
     }
     wg_barrier();
-    if (grp == 1) wg_barrier();  // second group: one phase behind
 
     // per-lane LDS byte offsets of the operand fragments inside ring slot 0; ring slot, 32-key
     // block and 16-row group are compile-time displacements on top (the swizzle has period 16 rows)
@@ -241,12 +241,15 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                 }
             }
         }
-        // tile T+1 is first read by group 0 right after the second barrier of this step
+        // The one workgroup barrier of this tile: the second group takes it here, between its
+        // matrix and vector phase, the first group at the end of the step.  Both groups therefore
+        // run M(T) in the same interval (same ring slots), but the second group's X(T) falls into
+        // the next one, next to the first group's M(T+1).  Tile T+1 is first read after it.
         if (grp == 1) {
             if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
             else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+            wg_barrier();
         }
-        wg_barrier();
 
         // ---------------- vector phase X(T)
         if (any_act) {
@@ -317,8 +320,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
             if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
             else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
             if (wv == 0 && T + 1 < ntiles && T >= 1) publish_gate(T + 1);  // tiles 0, 1: prologue
+            wg_barrier();
         }
-        wg_barrier();
     };
     static_assert(kRing == 4, "the tile loop is unrolled over the ring");
     // T = ntiles is the drain step (only the PV product of the last tile)
@@ -331,7 +334,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         if (T + 3 > ntiles) break;
         tile_step(std::integral_constant<int, 3>{}, T + 3);
     }
-    if (grp == 0) wg_barrier();  // matches the extra barrier the second group started with
 
     // ---- epilogue: O = O^T / l, L = ln2 * (m*sl + log2 l) - (c_t - c_base)
     const float lt = xhalf_sum(l);  // the two halves of the wave hold complementary keys
