@@ -69,41 +69,48 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     extern __shared__ __align__(16) char smem_raw[];
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
-    const int tile = xcd_remap(blockIdx.x, total_tiles);
-    const int bh = tile / num_qtiles;
-    const int q0 = (tile % num_qtiles) * BR;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = wv >> 2;  // waves wv and wv + 4 share a SIMD and run in opposite phases
     const int h = lane >> 5, lq = lane & 31;
     const float sl = scale_log2;
     const float inv_scale = kLog2e / scale_log2;
-
-    const size_t head_off = (size_t)bh * N * D;
-    const char* Kh = reinterpret_cast<const char*>(K + head_off);
-    const char* Vh = reinterpret_cast<const char*>(V + head_off);
-    const float* ch = c + (size_t)bh * N;
-    const float cbase = ch[q0];
-
-    // the two waves of a SIMD take adjacent 32-query slabs, so their bands differ by one block
-    const int qw0 = q0 + 64 * (wv & 3) + 32 * grp;  // first query of this wave
-    const int t = qw0 + lq;
-
-    // Q^T fragments (B operand), resident for the whole tile loop (rows past N read row N-1)
-    bf16x8 qf[KC];
-    {
-        const bf16_t* qp = Q + head_off + (size_t)min(t, N - 1) * D + 8 * h;
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) qf[kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
-    }
-    const float cq = ch[min(t, N - 1)] - cbase;
-
-    // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
-    const int k_lo = max(0, q0 - w + 1);
-    const int k_hi = min(N, q0 + BR) - 1;
-    const int j_lo = k_lo / kTileRows, j_hi = k_hi / kTileRows;
-    const int ntiles = j_hi - j_lo + 1;
     const int jfull = N / kTileRows;  // tiles below jfull have all 64 rows inside the sequence
+
+    // Persistent workgroups: workgroup b takes the query tiles xcd_remap(b) + k * gridDim.x, so the
+    // loads of the next tile are issued before the results of the current one are stored.
+    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    int bh, q0, qw0, t, j_lo, j_hi, ntiles;
+    size_t head_off;
+    const char *Kh, *Vh;
+    const float* ch;
+    float cbase, cq;
+    bf16x8 qf[KC];  // Q^T fragments (B operand), resident for the whole tile loop
+    auto set_tile = [&](int tl) __attribute__((always_inline)) {
+        bh = tl / num_qtiles;
+        q0 = (tl % num_qtiles) * BR;
+        head_off = (size_t)bh * N * D;
+        Kh = reinterpret_cast<const char*>(K + head_off);
+        Vh = reinterpret_cast<const char*>(V + head_off);
+        ch = c + (size_t)bh * N;
+        cbase = ch[q0];
+        // the two waves of a SIMD take adjacent 32-query slabs, so their bands differ by one block
+        qw0 = q0 + 64 * (wv & 3) + 32 * grp;  // first query of this wave
+        t = qw0 + lq;
+        {  // rows past N read row N-1
+            const bf16_t* qp = Q + head_off + (size_t)min(t, N - 1) * D + 8 * h;
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) qf[kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
+        }
+        cq = ch[min(t, N - 1)] - cbase;
+        // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
+        const int k_lo = max(0, q0 - w + 1);
+        const int k_hi = min(N, q0 + BR) - 1;
+        j_lo = k_lo / kTileRows;
+        j_hi = k_hi / kTileRows;
+        ntiles = j_hi - j_lo + 1;
+    };
+    set_tile(tile);
 
     Loader loader;
     loader.init(wv, lane);
@@ -122,24 +129,25 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     };
 
     f32x16 o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
-    float m = kNegBig, l = 0.0f;
-
-    issue_tile(0);
-    if (ntiles > 1) issue_tile(1);
-    // the first step multiplies pf = 0 with the last ring slot: make it finite
-    for (int o16 = tid * 16; o16 < kTileRows * D * 2; o16 += kFwdThreads * 16)
-        *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + o16) = f32x4{0.f, 0.f, 0.f, 0.f};
-    __builtin_amdgcn_s_waitcnt(0);
-    if (wv == 0) {
-        publish_gate(0);
-        if (ntiles > 1) publish_gate(1);
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-    }
-    wg_barrier();
+    float m, l;
+    // first two key tiles of the current query tile in flight, everything else of the ring idle
+    auto open_tile = [&]() __attribute__((always_inline)) {
+        issue_tile(0);
+        if (ntiles > 1) issue_tile(1);
+    };
+    auto start_tile = [&]() __attribute__((always_inline)) {
+        // the first step multiplies pf = 0 with the last ring slot: make it finite
+        for (int o16 = tid * 16; o16 < kTileRows * D * 2; o16 += kFwdThreads * 16)
+            *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + o16) = f32x4{0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_s_waitcnt(0);
+        if (wv == 0) {
+            publish_gate(0);
+            if (ntiles > 1) publish_gate(1);
+        }
+        wg_barrier();
+    };
+    open_tile();
+    start_tile();
 
     // per-lane LDS byte offsets of the operand fragments inside ring slot 0; ring slot, 32-key
     // block and 16-row group are compile-time displacements on top (the swizzle has period 16 rows)
@@ -183,9 +191,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 
     f32x16 s[2];     // S^T of the two blocks of the current tile (0: upper 32 keys, 1: lower)
     u32x4 pf[2][2];  // their probabilities as B operands (bf16 pairs)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
-    bool pending = false;  // the previous tile left a P that still has to be multiplied into O
+    bool pending;    // the previous tile left a P that still has to be multiplied into O
     constexpr float kBig = 1.152921504606846976e18f;  // 2^60
 
     // one key tile; the ring slot is a compile-time constant so that every LDS address is a
@@ -324,6 +330,16 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         }
     };
     static_assert(kRing == 4, "the tile loop is unrolled over the ring");
+    for (;;) {  // query tiles of this workgroup
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
+    m = kNegBig;
+    l = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
+    pending = false;
     // T = ntiles is the drain step (only the PV product of the last tile)
     for (int T = 0; T <= ntiles; T += 4) {
         tile_step(std::integral_constant<int, 0>{}, T);
@@ -335,11 +351,21 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         tile_step(std::integral_constant<int, 3>{}, T + 3);
     }
 
+    // all LDS reads of this query tile are done (last barrier): open the next one before storing
+    const int t_done = t, bh_done = bh;
+    const size_t head_done = head_off;
+    const float cq_done = cq;
+    const bool more = tile + (int)gridDim.x < total_tiles;
+    if (more) {
+        tile += gridDim.x;
+        set_tile(tile);
+        open_tile();
+    }
     // ---- epilogue: O = O^T / l, L = ln2 * (m*sl + log2 l) - (c_t - c_base)
     const float lt = xhalf_sum(l);  // the two halves of the wave hold complementary keys
-    if (t < N) {
+    if (t_done < N) {
         const float inv = 1.0f / lt;
-        bf16_t* orow = O + head_off + (size_t)t * D;
+        bf16_t* orow = O + head_done + (size_t)t_done * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -348,7 +374,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                             o[db][4 * g + 3] * inv};
                 *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(o4, bf16x4);
             }
-        if (h == 0) L[(size_t)bh * N + t] = (m * sl + fast_log2(lt)) * kLn2 - cq;
+        if (h == 0) L[(size_t)bh_done * N + t_done] = (m * sl + fast_log2(lt)) * kLn2 - cq_done;
+    }
+    if (!more) break;
+    start_tile();
     }
 }
 
@@ -364,8 +393,16 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    static int num_cu = 0;
+    if (num_cu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cu <= 0)
+            num_cu = 256;
+    }
+    const int grid = total < num_cu ? total : num_cu;  // one resident workgroup per CU
     ProfScope prof(kKernForward, s);
-    hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(total), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
+    hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(grid), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w,
                        scale * kLog2e, num_qtiles, total);
     return hipGetLastError();
