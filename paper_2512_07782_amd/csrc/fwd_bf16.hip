@@ -79,7 +79,12 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 
     // Persistent workgroups: workgroup b takes the query tiles xcd_remap(b) + k * gridDim.x, so the
     // loads of the next tile are issued before the results of the current one are stored.
-    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    // (the slot inside a step is rotated from step to step so that the short tiles at the ends of a
+    // head do not always fall to the same workgroups)
+    const int wg_slot = xcd_remap(blockIdx.x, gridDim.x);
+    int wg_step = 0;
+    auto tile_of = [&](int k) { return k * (int)gridDim.x + (wg_slot + 37 * k) % (int)gridDim.x; };
+    int tile = tile_of(0);
     int bh, q0, qw0, t, j_lo, j_hi, ntiles;
     size_t head_off;
     const char *Kh, *Vh;
@@ -355,9 +360,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const int t_done = t, bh_done = bh;
     const size_t head_done = head_off;
     const float cq_done = cq;
-    const bool more = tile + (int)gridDim.x < total_tiles;
+    const bool more = tile_of(wg_step + 1) < total_tiles;
     if (more) {
-        tile += gridDim.x;
+        tile = tile_of(++wg_step);
         set_tile(tile);
         open_tile();
     }
