@@ -51,9 +51,12 @@ def _load() -> ctypes.CDLL:
                                                _dp, _dp, _dp, _dp, _dp]
         lib.gfwa_oracle_dalpha_from_dc.argtypes = [_dp, _dp, L]
         lib.gfwa_oracle_dalpha_direct.argtypes = [_dp, _dp, L, L]
+        lib.gfwa_oracle_gate_activation.argtypes = [_dp, _dp, D, _dp, L]
+        lib.gfwa_oracle_gate_activation_backward.argtypes = [_dp, _dp, D, _dp, _dp, _dp, L]
         for f in ("gfwa_oracle_prefix", "gfwa_oracle_forward_c", "gfwa_oracle_forward",
                   "gfwa_oracle_backward_c", "gfwa_oracle_dalpha_from_dc",
-                  "gfwa_oracle_dalpha_direct"):
+                  "gfwa_oracle_dalpha_direct", "gfwa_oracle_gate_activation",
+                  "gfwa_oracle_gate_activation_backward"):
             getattr(lib, f).restype = None
         _lib = lib
     return _lib
@@ -94,6 +97,24 @@ def gate_prefix(alpha) -> np.ndarray:
 # --------------------------------------------------------------------------
 # forward (Sec. 3.2 score, Alg. 2 outputs)
 # --------------------------------------------------------------------------
+def gate_activation(h, beta, eps: float) -> np.ndarray:
+    """alpha = softplus(beta * h) / (beta + eps), elementwise (Sec. 3.2; Alg. 1 on-chip steps)."""
+    h, beta = _f64(h), _f64(beta)
+    assert h.shape == beta.shape
+    alpha = np.empty_like(h)
+    _load().gfwa_oracle_gate_activation(_p(h), _p(beta), float(eps), _p(alpha), h.size)
+    return alpha
+
+
+def gate_activation_backward(h, beta, eps: float, dalpha):
+    """(dh, dbeta) for a given d(alpha): the chain rule on the definition of the gate."""
+    h, beta, dalpha = _f64(h), _f64(beta), _f64(dalpha)
+    assert h.shape == beta.shape == dalpha.shape
+    dh, dbeta = np.empty_like(h), np.empty_like(h)
+    _load().gfwa_oracle_gate_activation_backward(_p(h), _p(beta), float(eps), _p(dalpha), _p(dh), _p(dbeta), h.size)
+    return dh, dbeta
+
+
 def forward_from_c(Q, K, V, c, w: int, scale: float, return_P: bool = False):
     """O, L (and optionally the band of P as [.., N, min(w,N)]) from a given prefix c."""
     lib = _load()

@@ -226,3 +226,43 @@ void gfwa_oracle_dalpha_direct(const double *dS_band, double *dalpha, long N, lo
         dalpha[q] = acc;
     }
 }
+
+/*
+ * Gate activation (Sec. 3.2, the equation that defines alpha from the pre-activation h and the
+ * amplitude beta; Alg. 1, the on-chip steps with the overflow-safe softplus; Sec. 3.3 puts the
+ * small epsilon into the denominator):
+ *
+ *   z = beta * h,  nu = max(z, 0),  softplus(z) = nu + log(exp(z - nu) + exp(-nu))
+ *   alpha = softplus(z) / (beta + eps)
+ *
+ * n independent elements.
+ */
+void gfwa_oracle_gate_activation(const double *h, const double *beta, double eps, double *alpha,
+                                 long n) {
+    for (long i = 0; i < n; ++i) {
+        const double z = beta[i] * h[i];
+        const double nu = z > 0.0 ? z : 0.0;
+        const double sp = nu + log(exp(z - nu) + exp(-nu));
+        alpha[i] = sp / (beta[i] + eps);
+    }
+}
+
+/*
+ * Its derivative (chain rule on the definition above; the paper states no listing for it):
+ * with s = softplus(z), sigma = d softplus / dz = 1 / (1 + exp(-z)),
+ *
+ *   d alpha / d h    = sigma * beta / (beta + eps)
+ *   d alpha / d beta = sigma * h / (beta + eps) - s / (beta + eps)^2
+ */
+void gfwa_oracle_gate_activation_backward(const double *h, const double *beta, double eps,
+                                          const double *dalpha, double *dh, double *dbeta, long n) {
+    for (long i = 0; i < n; ++i) {
+        const double z = beta[i] * h[i];
+        const double nu = z > 0.0 ? z : 0.0;
+        const double sp = nu + log(exp(z - nu) + exp(-nu));
+        const double sig = z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z));
+        const double be = beta[i] + eps;
+        dh[i] = dalpha[i] * sig * beta[i] / be;
+        dbeta[i] = dalpha[i] * (sig * h[i] / be - sp / (be * be));
+    }
+}
