@@ -43,8 +43,11 @@ def test_positive_and_monotone_in_h(oracle):
     h = np.linspace(-20, 20, 401)
     for b in (0.1, 1.0, 7.0):
         a = oracle.gate_activation(h, np.full_like(h, b), 1e-6)
-        assert (a > 0).all()
-        assert (np.diff(a) > 0).all()
+        # 1 + exp(z) rounds to 1 below z ~ -36.7, where the form of Alg. 1 returns exactly 0
+        assert (a >= 0).all() and (np.diff(a) >= 0).all()
+        live = b * h > -30
+        assert (a[live] > 0).all()
+        assert (np.diff(a[live]) > 0).all()
 
 
 def test_amplitude_limits(oracle):
