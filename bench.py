@@ -24,6 +24,40 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
 
 
+def gate_only(args, g, torch) -> int:
+    """The memory-bound gate kernels alone, at a size that saturates HBM; algorithmic bytes as in main()."""
+    B, H, N = (int(x) for x in args.gate_only.split(","))
+    gen = torch.Generator(device="cuda:0").manual_seed(1)
+    hpre = torch.randn(B, H, N, device="cuda:0", generator=gen) - 1.0
+    beta = torch.exp(0.5 * torch.randn(B, H, N, device="cuda:0", generator=gen))
+    out1, out2, out3 = torch.empty_like(hpre), torch.empty_like(hpre), torch.empty_like(hpre)
+    calls = {
+        "gate_prefix_scan": (8.0, lambda: g.gfwa_gate_prefix(hpre, out1)),
+        "gate_activation_prefix_scan": (12.0, lambda: g.gfwa_gate_activation_prefix(hpre, beta, args.gate_eps, out1)),
+        "gate_activation_bwd": (20.0, lambda: g.gfwa_gate_activation_backward(hpre, beta, args.gate_eps, out1,
+                                                                               out2, out3)),
+        "plain_copy": (8.0, lambda: out2.copy_(hpre)),
+    }
+    res = {}
+    for name, (bpe, fn) in calls.items():
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        gbs = bpe * B * H * N / ms / 1e6
+        res[name] = {"avg_ms": round(ms, 5), "bytes_per_element": bpe, "achieved": round(gbs, 1), "unit": "GB/s",
+                     "peak": PEAK_HBM_GBS, "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    print(json.dumps({"metric": "gate kernels, algorithmic GB/s", "shape": [B, H, N], "dtype": "f32",
+                      "steps": args.steps, "warmup": args.warmup, "data": "synthetic", "kernels": res}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -31,6 +65,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="long_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--from-preactivation", action="store_true",
+                    help="start the step from the gate pre-activation h and amplitude beta instead of alpha: "
+                         "fused activation + prefix scan in front, activation backward (dh, dbeta) at the end")
+    ap.add_argument("--gate-eps", type=float, default=1e-6)
+    ap.add_argument("--gate-only", default=None, metavar="B,H,N",
+                    help="time only the memory-bound gate kernels (prefix scan, fused activation + prefix scan, "
+                         "gate-gradient scan, activation backward) on [B,H,N] fp32 tensors of this shape, "
+                         "e.g. 16,64,262144 (1 GiB per tensor), and print their GB/s instead of the usual line")
     ap.add_argument("--cpu-heads", type=int, default=32)
     ap.add_argument("--traffic-file", default=None,
                     help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: lines "
@@ -56,6 +98,8 @@ def main() -> int:
         return 2
     g.load_library()
     dev = "cuda:0"
+    if args.gate_only:
+        return gate_only(args, g, torch)
     wl = gi.WORKLOADS[args.workload]
     ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha", "dO")} if wl.backward else gi.make_inputs(wl)
     bf = wl.dtype == "bf16"
@@ -65,6 +109,9 @@ def main() -> int:
     alpha = to(ins["alpha"], False)
     B, H, N, d, w = wl.B, wl.H, wl.N, wl.d, wl.w
 
+    if args.from_preactivation:
+        hpre, beta = (to(x, False) for x in gi.make_gate_inputs(wl))
+        dh, dbeta = torch.empty_like(hpre), torch.empty_like(hpre)
     c = torch.empty_like(alpha)
     O = torch.empty_like(Q)
     L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
@@ -74,10 +121,15 @@ def main() -> int:
         ws = torch.empty(g.gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=dev)
 
     def step():
-        g.gfwa_gate_prefix(alpha, c)
+        if args.from_preactivation:
+            g.gfwa_gate_activation_prefix(hpre, beta, args.gate_eps, c)
+        else:
+            g.gfwa_gate_prefix(alpha, c)
         g.gfwa_forward(Q, K, V, c, w, wl.scale, O=O, L=L)
         if wl.backward:
             g.gfwa_backward(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ, dK=dK, dV=dV, dalpha=dalpha)
+            if args.from_preactivation:
+                g.gfwa_gate_activation_backward(hpre, beta, args.gate_eps, dalpha, dh, dbeta)
 
     if args.copy_calibration_mib > 0:
         src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device=dev)
@@ -111,6 +163,8 @@ def main() -> int:
         "bwd_dkv": ("mfma", 8.0 * bhn * w * d),     # S, dP, dV, dK products
         "bwd_dq": ("mfma", 2.0 * bhn * w * d),      # the dQ product; its S and dP are recomputation (bf16: also forms D)
         "gate_grad_scan": ("hbm", 12.0 * bhn),
+        "gate_activation_prefix_scan": ("hbm", 12.0 * bhn),   # h, beta in; c out
+        "gate_activation_bwd": ("hbm", 20.0 * bhn),           # h, beta, dalpha in; dh, dbeta out
     }
     kernels = {}
     for name, (tot, cnt) in prof.items():
@@ -142,7 +196,8 @@ def main() -> int:
               "fwd_tflops_exact": round(wl.flops_fwd_exact() / fwd_ms / 1e9, 2),
               "fwd_frac_bf16_peak": round(f_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
     if wl.backward:
-        bwd_ms = sum(kernels[k]["avg_ms"] for k in ("bwd_rowdot", "bwd_dkv", "bwd_dq", "gate_grad_scan") if k in kernels)
+        bwd_ms = sum(kernels[k]["avg_ms"] for k in ("bwd_rowdot", "bwd_dkv", "bwd_dq", "gate_grad_scan", "gate_activation_bwd")
+                     if k in kernels)
         detail.update({"bwd_ms": round(bwd_ms, 5), "bwd_tflops_nominal": round(f_bwd / bwd_ms / 1e9, 2),
                        "bwd_frac_bf16_peak": round(f_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)})
 
@@ -153,9 +208,15 @@ def main() -> int:
         heads = list(range(nh))
         sel = lambda x, tr: oracle.select_heads(x, heads, tr)
         t0 = time.perf_counter()
-        cs = oracle.gate_prefix(sel(ins["alpha"], 1))
+        if args.from_preactivation:
+            hb = [sel(x, 1) for x in gi.make_gate_inputs(wl)]
+            cs = oracle.gate_prefix(oracle.gate_activation(hb[0], hb[1], args.gate_eps))
+        else:
+            cs = oracle.gate_prefix(sel(ins["alpha"], 1))
         if wl.backward:
-            oracle.backward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, sel(ins["dO"], 2), w, wl.scale)
+            gr = oracle.backward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, sel(ins["dO"], 2), w, wl.scale)
+            if args.from_preactivation:
+                oracle.gate_activation_backward(hb[0], hb[1], args.gate_eps, gr["dalpha"].reshape(hb[0].shape))
         else:
             oracle.forward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, w, wl.scale)
         dt_cpu = time.perf_counter() - t0
@@ -170,8 +231,10 @@ def main() -> int:
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={B} H={H} N={N} d={d} w={w} {wl.dtype}, gate prefix + forward"
-                   + (" + backward" if wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS},
+        "config": {"workload": f"{wl.name}: B={B} H={H} N={N} d={d} w={w} {wl.dtype}, "
+                   + ("gate activation + prefix" if args.from_preactivation else "gate prefix") + " + forward"
+                   + (" + backward" if wl.backward else "")
+                   + (" + gate activation backward" if args.from_preactivation and wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS},
         "roofline": roofline, "cpu_baseline": cpu, "detail": detail, "kernels": kernels,
     }
     print(json.dumps(out))

@@ -54,6 +54,31 @@ typedef enum {
 int gfwa_gate_prefix(const float *alpha, float *c, int B, int H, int N, gfwa_stream_t stream);
 
 /*
+ * Gate preprocessing as a whole (paper Sec. 3.2, the equation that defines alpha from the gate
+ * pre-activation h and the amplitude beta; Alg. 1 complete: activation with the overflow-safe
+ * softplus, scan and carry in one pass; Sec. 3.3 "Gate Preprocessing via Fused Tiled Scan"):
+ *
+ *   alpha = softplus(beta * h) / (beta + eps),     c[b,h,t] = sum_{q <= t} alpha[b,h,q]
+ *
+ * hpre, beta: [B,H,N] fp32 (head-major, like alpha; beta > 0 expected, eps >= 0);  c: [B,H,N] fp32 out.
+ * Neither alpha nor beta*h is written to memory: 12 bytes of traffic per element.
+ */
+int gfwa_gate_activation_prefix(const float *hpre, const float *beta, float eps, float *c, int B, int H,
+                                int N, gfwa_stream_t stream);
+
+/*
+ * Its derivative (chain rule on the definition in Sec. 3.2; the paper prints no listing for it):
+ * from d(alpha) as gfwa_backward returns it,
+ *
+ *   dh    = dalpha * sigma(beta h) * beta / (beta + eps)
+ *   dbeta = dalpha * (sigma(beta h) * h / (beta + eps) - softplus(beta h) / (beta + eps)^2)
+ *
+ * hpre, beta, dalpha: [B,H,N] fp32;  dh, dbeta: [B,H,N] fp32 out.
+ */
+int gfwa_gate_activation_backward(const float *hpre, const float *beta, float eps, const float *dalpha,
+                                  float *dh, float *dbeta, int B, int H, int N, gfwa_stream_t stream);
+
+/*
  * Fused forward (paper Sec. 3.2, the gated score; Alg. 2).  For every (b,h) and query t:
  *
  *   S_ti = scale * <q_t, k_i> + (c_i - c_t)     for  max(0, t-w+1) <= i <= t
@@ -103,10 +128,11 @@ int gfwa_version(void);
  * Instrumentation (not part of the method): per-kernel timing with HIP events recorded on the
  * caller's stream around every kernel the library launches.  gfwa_profile_enable(1) clears the
  * records and starts recording (at most 8192 launches are kept), gfwa_profile_enable(0) stops.
- * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 6), the
- * summed duration in milliseconds and the number of launches; n must be >= 6.  Kernel ids:
+ * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 8), the
+ * summed duration in milliseconds and the number of launches; n must be >= 8.  Kernel ids:
  * 0 gate prefix scan, 1 forward, 2 backward row-dot (D), 3 backward dK/dV, 4 backward dQ,
- * 5 gate-gradient reverse scan; gfwa_profile_kernel_name gives the same as text.
+ * 5 gate-gradient reverse scan, 6 gate activation + prefix scan, 7 gate activation backward;
+ * gfwa_profile_kernel_name gives the same as text.
  * Not thread-safe; host memory only.
  */
 int gfwa_profile_enable(int on);

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     gfwa_backward,
     gfwa_backward_workspace_bytes,
     gfwa_forward,
+    gfwa_gate_activation_backward,
+    gfwa_gate_activation_prefix,
     gfwa_gate_prefix,
     gfwa_profile_enable,
     gfwa_profile_kernel_name,

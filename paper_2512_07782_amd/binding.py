@@ -18,10 +18,10 @@ _lib: Optional[ctypes.CDLL] = None
 
 GFWA_BF16, GFWA_F32 = 0, 1
 
-EXPORTS = ("gfwa_gate_prefix", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
+EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
-N_KERNELS = 6
+N_KERNELS = 8
 
 
 class GfwaError(RuntimeError):
@@ -46,6 +46,10 @@ def load_library() -> ctypes.CDLL:
     vp, fp, i, f = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lib.gfwa_gate_prefix.argtypes = [fp, fp, i, i, i, vp]
     lib.gfwa_gate_prefix.restype = i
+    lib.gfwa_gate_activation_prefix.argtypes = [fp, fp, ctypes.c_float, fp, i, i, i, vp]
+    lib.gfwa_gate_activation_prefix.restype = i
+    lib.gfwa_gate_activation_backward.argtypes = [fp, fp, ctypes.c_float, fp, fp, fp, i, i, i, vp]
+    lib.gfwa_gate_activation_backward.restype = i
     lib.gfwa_forward.argtypes = [i, vp, vp, vp, fp, vp, fp, i, i, i, i, i, f, vp]
     lib.gfwa_forward.restype = i
     lib.gfwa_backward_workspace_bytes.argtypes = [i, i, i, i, i, i]
@@ -114,6 +118,42 @@ def gfwa_gate_prefix(alpha: torch.Tensor, c: Optional[torch.Tensor] = None) -> t
     _need(c, (B, H, N), torch.float32, "c")
     _check(load_library().gfwa_gate_prefix(alpha.data_ptr(), c.data_ptr(), B, H, N, _stream()))
     return c
+
+
+def gfwa_gate_activation_prefix(hpre: torch.Tensor, beta: torch.Tensor, eps: float,
+                                c: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """c = cumsum_t softplus(beta * hpre) / (beta + eps);  hpre, beta, c: [B,H,N] fp32 on the GPU."""
+    if hpre.dim() != 3:
+        raise ValueError("hpre must be [B,H,N]")
+    B, H, N = hpre.shape
+    _need(hpre, (B, H, N), torch.float32, "hpre")
+    _need(beta, (B, H, N), torch.float32, "beta")
+    if c is None:
+        c = torch.empty_like(hpre)
+    _need(c, (B, H, N), torch.float32, "c")
+    _check(load_library().gfwa_gate_activation_prefix(hpre.data_ptr(), beta.data_ptr(), float(eps), c.data_ptr(),
+                                                      B, H, N, _stream()))
+    return c
+
+
+def gfwa_gate_activation_backward(hpre: torch.Tensor, beta: torch.Tensor, eps: float, dalpha: torch.Tensor,
+                                  dh: Optional[torch.Tensor] = None, dbeta: Optional[torch.Tensor] = None):
+    """(dh, dbeta) from d(alpha); all [B,H,N] fp32 on the GPU."""
+    if hpre.dim() != 3:
+        raise ValueError("hpre must be [B,H,N]")
+    B, H, N = hpre.shape
+    for name, t in (("hpre", hpre), ("beta", beta), ("dalpha", dalpha)):
+        _need(t, (B, H, N), torch.float32, name)
+    if dh is None:
+        dh = torch.empty_like(hpre)
+    if dbeta is None:
+        dbeta = torch.empty_like(hpre)
+    _need(dh, (B, H, N), torch.float32, "dh")
+    _need(dbeta, (B, H, N), torch.float32, "dbeta")
+    _check(load_library().gfwa_gate_activation_backward(hpre.data_ptr(), beta.data_ptr(), float(eps),
+                                                        dalpha.data_ptr(), dh.data_ptr(), dbeta.data_ptr(),
+                                                        B, H, N, _stream()))
+    return dh, dbeta
 
 
 def gfwa_forward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, c: torch.Tensor, w: int,

@@ -73,6 +73,25 @@ int gfwa_gate_prefix(const float* alpha, float* c, int B, int H, int N, gfwa_str
     return hip_status(gate_prefix(alpha, c, B * H, N, stream));
 }
 
+int gfwa_gate_activation_prefix(const float* hpre, const float* beta, float eps, float* c, int B, int H, int N,
+                                gfwa_stream_t stream) {
+    if (!hpre || !beta || !c) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, 0, 1, false)) return r;
+    if (!(eps >= 0.0f)) return GFWA_ERR_DIM;
+    if (!aligned(hpre, 4) || !aligned(beta, 4) || !aligned(c, 4)) return GFWA_ERR_ALIGN;
+    return hip_status(gate_activation_prefix(hpre, beta, eps, c, B * H, N, stream));
+}
+
+int gfwa_gate_activation_backward(const float* hpre, const float* beta, float eps, const float* dalpha, float* dh,
+                                  float* dbeta, int B, int H, int N, gfwa_stream_t stream) {
+    if (!hpre || !beta || !dalpha || !dh || !dbeta) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, 0, 1, false)) return r;
+    if (!(eps >= 0.0f)) return GFWA_ERR_DIM;
+    if (!aligned(hpre, 4) || !aligned(beta, 4) || !aligned(dalpha, 4) || !aligned(dh, 4) || !aligned(dbeta, 4))
+        return GFWA_ERR_ALIGN;
+    return hip_status(gate_activation_backward(hpre, beta, eps, dalpha, dh, dbeta, (size_t)B * H * N, stream));
+}
+
 int gfwa_forward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const float* c, void* O,
                  float* L, int B, int H, int N, int d, int w, float scale, gfwa_stream_t stream) {
     if (!Q || !K || !V || !c || !O || !L) return GFWA_ERR_NULL;
@@ -158,7 +177,8 @@ int gfwa_profile_read(float* total_ms, int* launches, int n) {
 
 const char* gfwa_profile_kernel_name(int k) {
     static const char* names[kKernCount] = {"gate_prefix_scan", "forward", "bwd_rowdot", "bwd_dkv", "bwd_dq",
-                                            "gate_grad_scan"};
+                                            "gate_grad_scan", "gate_activation_prefix_scan",
+                                            "gate_activation_bwd"};
     return (k >= 0 && k < kKernCount) ? names[k] : "";
 }
 

@@ -7,6 +7,10 @@ namespace gfwa {
 
 // c = inclusive prefix sum of alpha along N, one row per (b,h).
 hipError_t gate_prefix(const float* alpha, float* c, int rows, int N, hipStream_t s);
+hipError_t gate_activation_prefix(const float* hpre, const float* beta, float eps, float* c, int rows, int N,
+                                  hipStream_t s);
+hipError_t gate_activation_backward(const float* hpre, const float* beta, float eps, const float* dalpha,
+                                    float* dh, float* dbeta, size_t n, hipStream_t s);
 // dalpha = reverse inclusive prefix sum of (col - row) along N.
 hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
                           hipStream_t s);
@@ -25,7 +29,8 @@ hipError_t backward_f32(const float* Q, const float* K, const float* V, const fl
                         float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s);
 
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
-enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernCount };
+enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,
+                kKernGateActBwd, kKernCount };
 
 // RAII pair of HIP events around one kernel launch on stream s; a no-op unless profiling is on.
 struct ProfScope {

@@ -23,7 +23,8 @@ def declared_functions():
 
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
-    assert names == sorted(["gfwa_gate_prefix", "gfwa_forward", "gfwa_backward_workspace_bytes",
+    assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
     for n in names:
@@ -55,6 +56,12 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_gate_prefix(good, good, 0, 1, 8, None) == -2
     assert lib.gfwa_gate_prefix(good, good, 1, 1, -3, None) == -2
     assert lib.gfwa_gate_prefix(P(0x1002), good, 1, 1, 8, None) == -4
+    # gate activation
+    assert lib.gfwa_gate_activation_prefix(good, None, f, good, 1, 1, 8, None) == -1
+    assert lib.gfwa_gate_activation_prefix(good, good, ctypes.c_float(-1.0), good, 1, 1, 8, None) == -2
+    assert lib.gfwa_gate_activation_prefix(good, good, f, P(0x1002), 1, 1, 8, None) == -4
+    assert lib.gfwa_gate_activation_backward(good, good, f, good, good, None, 1, 1, 8, None) == -1
+    assert lib.gfwa_gate_activation_backward(good, good, f, good, good, good, 1, 0, 8, None) == -2
     # forward
     args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
                          kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]

@@ -75,6 +75,111 @@ def test_gate_prefix(g, oracle, B, H, N):
     np.testing.assert_array_equal(ones[0, 1], np.arange(1, N + 1, dtype=np.float64))
 
 
+GATE_EPS = 1e-6
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (2, 3, 37), (1, 2, 4096), (2, 2, 4099), (1, 3, 16384),
+                                   (1, 1, 70001)])
+def test_gate_activation_prefix(g, oracle, B, H, N):
+    note("gate_activation_prefix", B, H, N)
+    wl = gi.custom("gact", B, H, N, 64, 8, alpha_mu=-1.0, index=8)
+    h, beta = gi.make_gate_inputs(wl)
+    c = host(g.gfwa_gate_activation_prefix(dev(h, "f32"), dev(beta, "f32"), GATE_EPS))
+    alpha = oracle.gate_activation(h, beta, GATE_EPS)
+    ref = oracle.gate_prefix(alpha)
+    # each alpha within a few fp32 ulp of itself (exp, log1p, add, divide), summed, plus the scan's own rounding
+    assert np.abs(c - ref).max() <= 8 * np.finfo(np.float32).eps * ref.max()
+    # the fused call and activation-free scan of the oracle's alpha agree to the same bar
+    c2 = host(g.gfwa_gate_prefix(dev(alpha.astype(np.float32), "f32")))
+    assert np.abs(c - c2).max() <= 8 * np.finfo(np.float32).eps * ref.max()
+
+
+def test_gate_activation_elementwise(g, oracle):
+    # rows of length 1: c is alpha itself, so the activation is checked element by element, over
+    # pre-activations from deeply negative (alpha ~ e^z, where the rounding of 1 + e^z would show) to large
+    n = 1 << 16
+    z = np.linspace(-80.0, 40.0, n)
+    beta = np.exp(0.5 * gi.normal(4242, (n,))).astype(np.float32)
+    h = (z / beta).astype(np.float32)
+    shape = (256, n // 256, 1)
+    a = host(g.gfwa_gate_activation_prefix(dev(h.reshape(shape), "f32"), dev(beta.reshape(shape), "f32"), GATE_EPS))
+    ref = oracle.gate_activation(h.reshape(shape), beta.reshape(shape), GATE_EPS)
+    # the oracle takes the logarithm of 1 + e^z as Alg. 1 writes it, in fp64: that sum is rounded to
+    # 2^-53, so below z ~ -30 the oracle's own value is the less accurate one (it is exactly 0 from -37 on)
+    floor = 2.0 ** -52 / (beta.reshape(shape).astype(np.float64) + GATE_EPS)
+    far = z.reshape(shape) > -20
+    rel = np.abs(a - ref)[far] / ref[far]
+    note(f"  alpha worst relative error for z > -20: {rel.max():.3e} ({rel.max() / np.finfo(np.float32).eps:.1f} ulp)")
+    # z = beta h is rounded to fp32 on the GPU (relative 2^-24) and d(log alpha)/dz <= 1 for z < 0,
+    # so a small alpha ~ e^z inherits |z| half-ulps from its argument on top of the arithmetic's few ulp
+    zz = z.reshape(shape)
+    assert (np.abs(a - ref) <= np.finfo(np.float32).eps * ref * (8 + np.maximum(-zz, 0)) + floor).all()
+
+
+def test_gate_activation_extremes(g, oracle):
+    # saturated, dead and zero pre-activations, tiny and large amplitudes: no overflow, alpha >= 0
+    h = np.array([[[-200.0, -30.0, -1e-3, 0.0, 1e-3, 30.0, 200.0, 3e4] * 5]], dtype=np.float32)
+    beta = np.repeat(np.array([1e-3, 0.5, 1.0, 8.0, 100.0], dtype=np.float32), 8).reshape(1, 1, -1)
+    c = host(g.gfwa_gate_activation_prefix(dev(h, "f32"), dev(beta, "f32"), GATE_EPS))
+    ref = oracle.gate_prefix(oracle.gate_activation(h, beta, GATE_EPS))
+    assert np.isfinite(c).all() and (c >= 0).all()
+    assert np.abs(c - ref).max() <= 8 * np.finfo(np.float32).eps * ref.max()
+    dal = np.ones_like(h)
+    dh, dbeta = (host(x) for x in g.gfwa_gate_activation_backward(dev(h, "f32"), dev(beta, "f32"), GATE_EPS,
+                                                                  dev(dal, "f32")))
+    rh, rb = oracle.gate_activation_backward(h, beta, GATE_EPS, dal)
+    assert np.isfinite(dh).all() and np.isfinite(dbeta).all()
+    np.testing.assert_allclose(dh, rh, rtol=1e-5, atol=1e-30)
+    be = beta.astype(np.float64) + GATE_EPS
+    terms = np.abs(h) / be + (np.maximum(beta.astype(np.float64) * h, 0) + 0.7) / be ** 2
+    assert (np.abs(dbeta - rb) <= 16 * np.finfo(np.float32).eps * terms + 1e-30).all()
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (2, 3, 37), (1, 2, 4099), (4, 8, 16384), (1, 1, 4194309)])
+def test_gate_activation_backward(g, oracle, B, H, N):
+    note("gate_activation_backward", B, H, N)
+    wl = gi.custom("gactb", B, H, N, 64, 8, alpha_mu=-1.0, index=9)
+    h, beta = gi.make_gate_inputs(wl)
+    dal = gi.normal(wl.seed("dO"), h.shape).astype(np.float32)
+    dh, dbeta = (host(x) for x in g.gfwa_gate_activation_backward(dev(h, "f32"), dev(beta, "f32"), GATE_EPS,
+                                                                  dev(dal, "f32")))
+    rh, rb = oracle.gate_activation_backward(h, beta, GATE_EPS, dal)
+    np.testing.assert_allclose(dh, rh, rtol=1e-5, atol=1e-30)
+    # dbeta is a difference of two terms: a few fp32 ulp of an upper bound of their magnitudes
+    be = beta.astype(np.float64) + GATE_EPS
+    terms = np.abs(dal) * (np.abs(h) / be + (np.maximum(beta.astype(np.float64) * h, 0) + 0.7) / be ** 2)
+    assert (np.abs(dbeta - rb) <= 16 * np.finfo(np.float32).eps * terms + 1e-30).all()
+    assert rel_l2(dbeta, rb) <= 1e-6 and rel_l2(dh, rh) <= 1e-6
+
+
+@pytest.mark.parametrize("B,H,N,d,w", [(1, 2, 300, 128, 64), (2, 2, 1030, 64, 256)])
+def test_chain_from_gate_preactivation_bf16(g, oracle, B, H, N, d, w):
+    # h, beta -> c (fused) -> forward -> backward -> dalpha -> dh, dbeta, all on the GPU, against the
+    # oracle's chain from the same inputs
+    note("chain from h, beta", B, H, N, d, w)
+    wl = gi.custom("gchain", B, H, N, d, w, "bf16", alpha_mu=-1.0, index=10, backward=True)
+    ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "dO")}
+    h, beta = gi.make_gate_inputs(wl)
+    alpha = oracle.gate_activation(h, beta, GATE_EPS)
+    c_ref = oracle.gate_prefix(alpha)
+    O_ref, L_ref = oracle.forward_from_c(ins["Q"], ins["K"], ins["V"], c_ref, wl.w, wl.scale)
+    ref = oracle.backward_from_c(ins["Q"], ins["K"], ins["V"], c_ref, ins["dO"], wl.w, wl.scale)
+    ref_dh, ref_dbeta = oracle.gate_activation_backward(h, beta, GATE_EPS, ref["dalpha"].reshape(h.shape))
+    Qd, Kd, Vd, dOd = (dev(ins[t], "bf16") for t in ("Q", "K", "V", "dO"))
+    hd, bd = dev(h, "f32"), dev(beta, "f32")
+    cd = g.gfwa_gate_activation_prefix(hd, bd, GATE_EPS)
+    Od, Ld = g.gfwa_forward(Qd, Kd, Vd, cd, wl.w, wl.scale)
+    dQ, dK, dV, dalpha = g.gfwa_backward(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale)
+    dh, dbeta = g.gfwa_gate_activation_backward(hd, bd, GATE_EPS, dalpha)
+    torch.cuda.synchronize()
+    LAST["c_span"] = float(c_ref.max())
+    check_bf16_forward(host(Od), host(Ld), O_ref, L_ref, tag="chain")
+    for name, got, want in (("dh", dh, ref_dh), ("dbeta", dbeta, ref_dbeta)):
+        r = rel_l2(host(got), want)
+        note(f"  chain {name} rel-L2 {r:.3e}")
+        assert r <= 1e-2, (name, r)
+
+
 # ------------------------------------------------------------------------------------------
 # forward
 # ------------------------------------------------------------------------------------------
