@@ -174,6 +174,36 @@ def backward(Q, K, V, alpha, dO, w: int, scale: float, return_dS: bool = False) 
     return backward_from_c(Q, K, V, gate_prefix(alpha), dO, w, scale, return_dS=return_dS)
 
 
+# --------------------------------------------------------------------------
+# grouped-query layout (App. "Additional Experiment Details": heads_per_gqa_group in the training
+# tables).  The paper fixes only the group size; the reading taken is the usual one: query head h
+# attends to the keys and values of head h // G, the gate belongs to the query head.  The definition
+# written out: repeat each key/value head G times, apply the multi-head definition, and sum the
+# key/value gradients over the G query heads that read the same head.
+# --------------------------------------------------------------------------
+def _repeat_kv(X, H: int) -> np.ndarray:
+    X = _f64(X)
+    B, Hkv = X.shape[0], X.shape[1]
+    assert X.ndim == 4 and H % Hkv == 0, "K, V must be [B,Hkv,N,d] with Hkv dividing H"
+    return np.repeat(X, H // Hkv, axis=1)
+
+
+def forward_gqa_from_c(Q, K, V, c, w: int, scale: float):
+    """O, L for Q [B,H,N,d], K, V [B,Hkv,N,d], c [B,H,N]."""
+    H = np.shape(Q)[1]
+    return forward_from_c(Q, _repeat_kv(K, H), _repeat_kv(V, H), c, w, scale)
+
+
+def backward_gqa_from_c(Q, K, V, c, dO, w: int, scale: float) -> Dict[str, np.ndarray]:
+    """dQ [B,H,N,d], dK, dV [B,Hkv,N,d], dc, dalpha [B,H,N]."""
+    B, H, N, d = np.shape(Q)
+    Hkv = np.shape(K)[1]
+    out = backward_from_c(Q, _repeat_kv(K, H), _repeat_kv(V, H), c, dO, w, scale)
+    for k in ("dK", "dV"):
+        out[k] = out[k].reshape(B, Hkv, H // Hkv, N, d).sum(axis=2)
+    return out
+
+
 def dalpha_direct(dS_band, w: int) -> np.ndarray:
     """d(alpha) from the band of dS without going through dc (tiny N only)."""
     lib = _load()
