@@ -116,18 +116,21 @@ def main() -> int:
     O = torch.empty_like(Q)
     L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
     if wl.backward:
-        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
         dalpha = torch.empty_like(alpha)
         ws = torch.empty(g.gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=dev)
+
+    gqa = wl.Hkv != wl.H   # grouped-query workloads go through the entry points that take [B,Hkv,N,d] keys
+    fwd, bwd = (g.gfwa_forward_gqa, g.gfwa_backward_gqa) if gqa else (g.gfwa_forward, g.gfwa_backward)
 
     def step():
         if args.from_preactivation:
             g.gfwa_gate_activation_prefix(hpre, beta, args.gate_eps, c)
         else:
             g.gfwa_gate_prefix(alpha, c)
-        g.gfwa_forward(Q, K, V, c, w, wl.scale, O=O, L=L)
+        fwd(Q, K, V, c, w, wl.scale, O=O, L=L)
         if wl.backward:
-            g.gfwa_backward(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ, dK=dK, dV=dV, dalpha=dalpha)
+            bwd(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ, dK=dK, dV=dV, dalpha=dalpha)
             if args.from_preactivation:
                 g.gfwa_gate_activation_backward(hpre, beta, args.gate_eps, dalpha, dh, dbeta)
 
@@ -204,9 +207,13 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        nh = min(args.cpu_heads, B * H)
+        G = H // wl.Hkv
+        nh = max(G, min(args.cpu_heads, B * H) // G * G)     # whole groups
         heads = list(range(nh))
         sel = lambda x, tr: oracle.select_heads(x, heads, tr)
+        # the first nh query heads and the nh / G key/value heads they read, as one batch entry
+        selq = lambda x: sel(x, 2).reshape(1, nh, N, d)
+        selk = lambda x: oracle.select_heads(x, list(range(nh // G)), 2).reshape(1, nh // G, N, d)
         t0 = time.perf_counter()
         if args.from_preactivation:
             hb = [sel(x, 1) for x in gi.make_gate_inputs(wl)]
@@ -214,11 +221,12 @@ def main() -> int:
         else:
             cs = oracle.gate_prefix(sel(ins["alpha"], 1))
         if wl.backward:
-            gr = oracle.backward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, sel(ins["dO"], 2), w, wl.scale)
+            gr = oracle.backward_gqa_from_c(selq(ins["Q"]), selk(ins["K"]), selk(ins["V"]), cs.reshape(1, nh, N),
+                                            selq(ins["dO"]), w, wl.scale)
             if args.from_preactivation:
                 oracle.gate_activation_backward(hb[0], hb[1], args.gate_eps, gr["dalpha"].reshape(hb[0].shape))
         else:
-            oracle.forward_from_c(sel(ins["Q"], 2), sel(ins["K"], 2), sel(ins["V"], 2), cs, w, wl.scale)
+            oracle.forward_gqa_from_c(selq(ins["Q"]), selk(ins["K"]), selk(ins["V"]), cs.reshape(1, nh, N), w, wl.scale)
         dt_cpu = time.perf_counter() - t0
         frac = nh / (B * H)
         cpu = {"value": round((f_fwd + f_bwd) * frac / dt_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.threads(),
@@ -231,7 +239,7 @@ def main() -> int:
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={B} H={H} N={N} d={d} w={w} {wl.dtype}, "
+        "config": {"workload": f"{wl.name}: B={B} H={H}" + (f" Hkv={wl.Hkv}" if gqa else "") + f" N={N} d={d} w={w} {wl.dtype}, "
                    + ("gate activation + prefix" if args.from_preactivation else "gate prefix") + " + forward"
                    + (" + backward" if wl.backward else "")
                    + (" + gate activation backward" if args.from_preactivation and wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS},

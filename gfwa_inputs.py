@@ -81,6 +81,11 @@ class Workload:
     alpha_mu: float = 0.0      # alpha = softplus(N(alpha_mu, 1))
     zero_gate_heads: Tuple[int, ...] = ()   # heads whose alpha is exactly 0
     backward: bool = False
+    kv_heads: int = 0          # key/value heads of the grouped-query layout; 0: one per query head
+
+    @property
+    def Hkv(self) -> int:
+        return self.kv_heads or self.H
 
     @property
     def scale(self) -> float:
@@ -112,6 +117,9 @@ WORKLOADS: Dict[str, Workload] = {
                  alpha_mu=1.0, zero_gate_heads=(0, 1, 2, 3)),
         Workload("train_bwd", 4, 4, 16, 8192, 128, 1024, "bf16", alpha_mu=-2.0, backward=True),
         Workload("long_bwd", 5, 1, 32, 16384, 128, 1024, "bf16", alpha_mu=-3.0, backward=True),
+        # grouped-query variants, 4 query heads per key/value head as in the paper's training tables
+        Workload("lm_gqa_bwd", 6, 4, 16, 4096, 64, 512, "bf16", alpha_mu=-2.0, backward=True, kv_heads=4),
+        Workload("long_gqa_bwd", 7, 1, 32, 16384, 128, 1024, "bf16", alpha_mu=-3.0, backward=True, kv_heads=8),
     ]
 }
 
@@ -139,10 +147,12 @@ def make_tensor(wl: Workload, tag: str, heads: Optional[np.ndarray] = None) -> n
         out = a
     else:
         std = wl.qkv_std if tag in ("Q", "K", "V") else 1.0
+        if tag in ("K", "V"):
+            BH = wl.B * wl.Hkv
         out = _store(normal(wl.seed(tag), (BH, wl.N, wl.d), std=std), wl.dtype)
     if heads is not None:
         return np.ascontiguousarray(out[np.asarray(heads)])
-    return out.reshape((wl.B, wl.H) + out.shape[1:])
+    return out.reshape((wl.B, BH // wl.B) + out.shape[1:])
 
 
 def make_gate_inputs(wl: Workload) -> Tuple[np.ndarray, np.ndarray]:

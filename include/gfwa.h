@@ -118,6 +118,22 @@ int gfwa_backward(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, 
                   float *dalpha, void *workspace, size_t workspace_bytes, int B, int H, int N,
                   int d, int w, float scale, gfwa_stream_t stream);
 
+/*
+ * Grouped-query layout of the two calls above (the group size heads_per_gqa_group of the paper's
+ * training configurations, App. "Additional Experiment Details"; the paper gives no formula for it, the
+ * usual meaning is taken): K, V, dK, dV are [B,Hkv,N,d] with Hkv dividing H, query head h reads the
+ * keys and values of head h / (H / Hkv), and dK, dV sum over the H / Hkv query heads that read a head.
+ * Everything per query head (Q, O, dO, dQ [B,H,N,d]; c, L, dalpha [B,H,N]; the workspace size) is as
+ * above; Hkv == H is exactly gfwa_forward / gfwa_backward.
+ */
+int gfwa_forward_gqa(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, const float *c,
+                     void *O, float *L, int B, int H, int Hkv, int N, int d, int w, float scale,
+                     gfwa_stream_t stream);
+int gfwa_backward_gqa(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, const void *O,
+                      const void *dO, const float *c, const float *L, void *dQ, void *dK, void *dV,
+                      float *dalpha, void *workspace, size_t workspace_bytes, int B, int H, int Hkv,
+                      int N, int d, int w, float scale, gfwa_stream_t stream);
+
 /* Static, human-readable text for a status code (for GFWA_ERR_HIP: the last HIP error text). */
 const char *gfwa_strerror(int code);
 

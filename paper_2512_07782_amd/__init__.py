@@ -7,8 +7,10 @@ memory and streams.
 from .binding import (  # noqa: F401
     GfwaError,
     gfwa_backward,
+    gfwa_backward_gqa,
     gfwa_backward_workspace_bytes,
     gfwa_forward,
+    gfwa_forward_gqa,
     gfwa_gate_activation_backward,
     gfwa_gate_activation_prefix,
     gfwa_gate_prefix,

@@ -19,6 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 GFWA_BF16, GFWA_F32 = 0, 1
 
 EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
+           "gfwa_forward_gqa", "gfwa_backward_gqa",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
 N_KERNELS = 8
@@ -57,6 +58,11 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_backward.argtypes = [i, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, ctypes.c_size_t,
                                   i, i, i, i, i, f, vp]
     lib.gfwa_backward.restype = i
+    lib.gfwa_forward_gqa.argtypes = [i, vp, vp, vp, fp, vp, fp, i, i, i, i, i, i, f, vp]
+    lib.gfwa_forward_gqa.restype = i
+    lib.gfwa_backward_gqa.argtypes = [i, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, ctypes.c_size_t,
+                                      i, i, i, i, i, i, f, vp]
+    lib.gfwa_backward_gqa.restype = i
     lib.gfwa_strerror.argtypes = [i]
     lib.gfwa_strerror.restype = ctypes.c_char_p
     lib.gfwa_version.argtypes = []
@@ -213,6 +219,72 @@ def gfwa_backward(Q, K, V, O, dO, c, L, w: int, scale: float, workspace: Optiona
                                         dK.data_ptr(), dV.data_ptr(), dalpha.data_ptr(),
                                         workspace.data_ptr(), ws_bytes, B, H, N, d, int(w), float(scale),
                                         _stream()))
+    return dQ, dK, dV, dalpha
+
+
+def _kv_heads(Q: torch.Tensor, K: torch.Tensor) -> int:
+    if Q.dim() != 4 or K.dim() != 4:
+        raise ValueError("Q must be [B,H,N,d] and K [B,Hkv,N,d]")
+    H, Hkv = Q.shape[1], K.shape[1]
+    if Hkv <= 0 or H % Hkv != 0:
+        raise ValueError(f"the number of key/value heads ({Hkv}) must divide the number of query heads ({H})")
+    return Hkv
+
+
+def gfwa_forward_gqa(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, c: torch.Tensor, w: int,
+                     scale: float, O: Optional[torch.Tensor] = None,
+                     L: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """gfwa_forward with K, V [B,Hkv,N,d]: query head h reads key/value head h // (H // Hkv)."""
+    Hkv = _kv_heads(Q, K)
+    B, H, N, d = Q.shape
+    dt = _dt(Q)
+    _need(Q, (B, H, N, d), Q.dtype, "Q")
+    for name, t in (("K", K), ("V", V)):
+        _need(t, (B, Hkv, N, d), Q.dtype, name)
+    _need(c, (B, H, N), torch.float32, "c")
+    if O is None:
+        O = torch.empty_like(Q)
+    if L is None:
+        L = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _need(O, (B, H, N, d), Q.dtype, "O")
+    _need(L, (B, H, N), torch.float32, "L")
+    _check(load_library().gfwa_forward_gqa(dt, Q.data_ptr(), K.data_ptr(), V.data_ptr(), c.data_ptr(),
+                                           O.data_ptr(), L.data_ptr(), B, H, Hkv, N, d, int(w), float(scale),
+                                           _stream()))
+    return O, L
+
+
+def gfwa_backward_gqa(Q, K, V, O, dO, c, L, w: int, scale: float, workspace: Optional[torch.Tensor] = None,
+                      dQ=None, dK=None, dV=None, dalpha=None):
+    """gfwa_backward with K, V, dK, dV [B,Hkv,N,d]; dK, dV sum over the query heads of a group."""
+    Hkv = _kv_heads(Q, K)
+    B, H, N, d = Q.shape
+    dt = _dt(Q)
+    for name, t in (("Q", Q), ("O", O), ("dO", dO)):
+        _need(t, (B, H, N, d), Q.dtype, name)
+    for name, t in (("K", K), ("V", V)):
+        _need(t, (B, Hkv, N, d), Q.dtype, name)
+    _need(c, (B, H, N), torch.float32, "c")
+    _need(L, (B, H, N), torch.float32, "L")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(K) if dV is None else dV
+    dalpha = torch.empty((B, H, N), dtype=torch.float32, device=Q.device) if dalpha is None else dalpha
+    _need(dQ, (B, H, N, d), Q.dtype, "dQ")
+    for name, t in (("dK", dK), ("dV", dV)):
+        _need(t, (B, Hkv, N, d), Q.dtype, name)
+    _need(dalpha, (B, H, N), torch.float32, "dalpha")
+    need = gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(load_library().gfwa_backward_gqa(dt, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                            dO.data_ptr(), c.data_ptr(), L.data_ptr(), dQ.data_ptr(),
+                                            dK.data_ptr(), dV.data_ptr(), dalpha.data_ptr(),
+                                            workspace.data_ptr(), ws_bytes, B, H, Hkv, N, d, int(w),
+                                            float(scale), _stream()))
     return dQ, dK, dV, dalpha
 
 

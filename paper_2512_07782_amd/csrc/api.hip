@@ -94,16 +94,22 @@ int gfwa_gate_activation_backward(const float* hpre, const float* beta, float ep
 
 int gfwa_forward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const float* c, void* O,
                  float* L, int B, int H, int N, int d, int w, float scale, gfwa_stream_t stream) {
+    return gfwa_forward_gqa(dt, Q, K, V, c, O, L, B, H, H, N, d, w, scale, stream);
+}
+
+int gfwa_forward_gqa(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const float* c, void* O,
+                     float* L, int B, int H, int Hkv, int N, int d, int w, float scale, gfwa_stream_t stream) {
     if (!Q || !K || !V || !c || !O || !L) return GFWA_ERR_NULL;
     if (int r = check_dims(B, H, N, d, w, true)) return r;
+    if (Hkv <= 0 || H % Hkv != 0) return GFWA_ERR_DIM;
     if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(c, 4) ||
         !aligned(L, 4))
         return GFWA_ERR_ALIGN;
     if (dt == GFWA_F32)
         return hip_status(forward_f32((const float*)Q, (const float*)K, (const float*)V, c, (float*)O, L,
-                                      B, H, N, d, w, scale, stream));
-    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, N, d, w, scale, stream));
+                                      B, H, Hkv, N, d, w, scale, stream));
+    return hip_status(forward_bf16(Q, K, V, c, O, L, B, H, Hkv, N, d, w, scale, stream));
 }
 
 size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
@@ -118,8 +124,17 @@ int gfwa_backward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, 
                   const void* dO, const float* c, const float* L, void* dQ, void* dK, void* dV,
                   float* dalpha, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, int w,
                   float scale, gfwa_stream_t stream) {
+    return gfwa_backward_gqa(dt, Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, workspace, workspace_bytes, B, H, H, N,
+                             d, w, scale, stream);
+}
+
+int gfwa_backward_gqa(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const void* O,
+                      const void* dO, const float* c, const float* L, void* dQ, void* dK, void* dV,
+                      float* dalpha, void* workspace, size_t workspace_bytes, int B, int H, int Hkv, int N,
+                      int d, int w, float scale, gfwa_stream_t stream) {
     if (!Q || !K || !V || !O || !dO || !c || !L || !dQ || !dK || !dV || !dalpha) return GFWA_ERR_NULL;
     if (int r = check_dims(B, H, N, d, w, true)) return r;
+    if (Hkv <= 0 || H % Hkv != 0) return GFWA_ERR_DIM;
     if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
     const void* mats[] = {Q, K, V, O, dO, dQ, dK, dV};
     for (const void* p : mats)
@@ -132,15 +147,16 @@ int gfwa_backward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, 
     if (dt == GFWA_F32)
         return hip_status(backward_f32((const float*)Q, (const float*)K, (const float*)V, (const float*)O,
                                        (const float*)dO, c, L, (float*)dQ, (float*)dK, (float*)dV, dalpha,
-                                       ws, B, H, N, d, w, scale, stream));
-    return hip_status(backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, d, w, scale, stream));
+                                       ws, B, H, Hkv, N, d, w, scale, stream));
+    return hip_status(
+        backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, d, w, scale, stream));
 }
 
 const char* gfwa_strerror(int code) {
     switch (code) {
         case GFWA_OK: return "ok";
         case GFWA_ERR_NULL: return "a required pointer is NULL";
-        case GFWA_ERR_DIM: return "invalid size: B, H, N, d must be > 0, w >= 1, within index range";
+        case GFWA_ERR_DIM: return "invalid size: B, H, N, d must be > 0, w >= 1, Hkv > 0 dividing H, within index range";
         case GFWA_ERR_UNSUPPORTED: return "unsupported head dimension (64 or 128) or dtype";
         case GFWA_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes matrices, 4 bytes vectors)";
         case GFWA_ERR_WORKSPACE: return "workspace missing or smaller than gfwa_backward_workspace_bytes()";

@@ -65,13 +65,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
     const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
-    float* __restrict__ dc_col, int N, int w, float scale, int num_ktiles, int total_tiles) {
+    float* __restrict__ dc_col, int N, int w, float scale, int num_ktiles, int total_tiles, int H, int G) {
     constexpr int BK = 128;  // keys per workgroup, 32 per wave
     constexpr int KC = D / 16, DB = D / 32;
     __shared__ DkvSmem<D> sm;
 
     const int tile = xcd_remap(blockIdx.x, total_tiles);
-    const int bh = tile / num_ktiles;
+    const int bkv = tile / num_ktiles;  // flat key/value head; its G query heads are visited in turn
     const int k0 = (tile % num_ktiles) * BK;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -79,13 +79,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     const float sl = scale * kLog2e;
     const float inv_scale = 1.0f / scale;
 
-    const size_t head_off = (size_t)bh * N * D;
-    const char* Qh = reinterpret_cast<const char*>(Q + head_off);
-    const char* Gh = reinterpret_cast<const char*>(dO + head_off);
-    const float* ch = c + (size_t)bh * N;
-    const float* Lh = L + (size_t)bh * N;
-    const float* Dh = Dv + (size_t)bh * N;
-    const float cbase = ch[k0];
+    const size_t head_off = (size_t)bkv * N * D;
+    const int Hkv = H / G;
+    const int bh0 = (bkv / Hkv) * H + (bkv % Hkv) * G;  // first query head of the group
 
     const int kw0 = k0 + 32 * wv;  // first key of this wave
     const int key = kw0 + lk;
@@ -100,7 +96,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
             vf[kc] = *reinterpret_cast<const bf16x8*>(V + roff + 16 * kc);
         }
     }
-    const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
 
     f32x16 dk_acc[DB], dv_acc[DB];
 #pragma unroll
@@ -110,7 +105,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
             dk_acc[db][v] = 0.f;
             dv_acc[db][v] = 0.f;
         }
-    float colsum = 0.f;
 
     // queries that can see a key of this tile: k0 <= t <= min(N-1, k0+BK-1+w-1)
     const int t_hi = (int)min((long)N - 1, (long)k0 + BK - 1 + (long)w - 1);
@@ -119,93 +113,107 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
 
     TilePairLoader<D> loader;
     loader.init(wv, lane);
-    // per-row vectors of query tile i, one row per thread of the first wave
-    float nl_stage = -kPosBig, d_stage = 0.f;
-    auto load_vec = [&](int i) {
-        if (tid < kTileRows) {
-            const int t = i * kTileRows + tid;
-            if (t < N) {
-                nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
-                d_stage = Dh[t];
-            } else {
-                nl_stage = -kPosBig;
-                d_stage = 0.f;
+    for (int qh = 0; qh < G; ++qh) {
+        const int bh = bh0 + qh;
+        const size_t qhead_off = (size_t)bh * N * D;
+        const char* Qh = reinterpret_cast<const char*>(Q + qhead_off);
+        const char* Gh = reinterpret_cast<const char*>(dO + qhead_off);
+        const float* ch = c + (size_t)bh * N;
+        const float* Lh = L + (size_t)bh * N;
+        const float* Dh = Dv + (size_t)bh * N;
+        const float cbase = ch[k0];
+        const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
+        float colsum = 0.f;
+        // per-row vectors of query tile i, one row per thread of the first wave
+        float nl_stage = -kPosBig, d_stage = 0.f;
+        auto load_vec = [&](int i) {
+            if (tid < kTileRows) {
+                const int t = i * kTileRows + tid;
+                if (t < N) {
+                    nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
+                    d_stage = Dh[t];
+                } else {
+                    nl_stage = -kPosBig;
+                    d_stage = 0.f;
+                }
             }
-        }
-    };
-    auto store_vec = [&](int buf) {
-        if (tid < kTileRows) {
-            sm.nl[buf][tid] = nl_stage;
-            sm.dvec[buf][tid] = d_stage;
-        }
-    };
-    loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
-    load_vec(i_lo);
-    store_vec(0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+        };
+        auto store_vec = [&](int buf) {
+            if (tid < kTileRows) {
+                sm.nl[buf][tid] = nl_stage;
+                sm.dvec[buf][tid] = d_stage;
+            }
+        };
+        loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
+        load_vec(i_lo);
+        store_vec(0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
 
-    for (int i = i_lo; i <= i_hi; ++i) {
-        const int buf = (i - i_lo) & 1;
-        if (i < i_hi) {
-            loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
-            load_vec(i + 1);
-        }
-        const char* qt = sm.qg.a[buf];
-        const char* gt = sm.qg.b[buf];
+        for (int i = i_lo; i <= i_hi; ++i) {
+            const int buf = (i - i_lo) & 1;
+            if (i < i_hi) {
+                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
+                load_vec(i + 1);
+            }
+            const char* qt = sm.qg.a[buf];
+            const char* gt = sm.qg.b[buf];
 #pragma unroll
-        for (int sb = 0; sb < kTileRows / 32; ++sb) {
-            const int qb0 = i * kTileRows + 32 * sb;
-            const bool act = (kw0 <= qb0 + 31) && (kw0 + 31 > qb0 - w) && (kw0 < N) && (qb0 < N);
-            if (!act) continue;
-            const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
+            for (int sb = 0; sb < kTileRows / 32; ++sb) {
+                const int qb0 = i * kTileRows + 32 * sb;
+                const bool act = (kw0 <= qb0 + 31) && (kw0 + 31 > qb0 - w) && (kw0 < N) && (qb0 < N);
+                if (!act) continue;
+                const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
 
-            // S[q][k] starts from the row term of the exponent; dP from zero
-            f32x16 s, dp;
-            acc_init_rows(s, sm.nl[buf], 32 * sb, h);
+                // S[q][k] starts from the row term of the exponent; dP from zero
+                f32x16 s, dp;
+                acc_init_rows(s, sm.nl[buf], 32 * sb, h);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+                for (int v = 0; v < 16; ++v) dp[v] = 0.f;
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
+                for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
-            f32x4 dvv[4];
+                for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
+                f32x4 dvv[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                dvv[g] = *reinterpret_cast<const f32x4*>(&sm.dvec[buf][32 * sb + 8 * g + 4 * h]);
-            float p[16], ds[16];
+                for (int g = 0; g < 4; ++g)
+                    dvv[g] = *reinterpret_cast<const f32x4*>(&sm.dvec[buf][32 * sb + 8 * g + 4 * h]);
+                float p[16], ds[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
-            if (!full) {
+                for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
+                if (!full) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = qb0 + acc_row(v, h);
+                        const bool keep = (key <= t) && (key > t - w);
+                        p[v] = keep ? p[v] : 0.f;
+                    }
+                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int t = qb0 + acc_row(v, h);
-                    const bool keep = (key <= t) && (key > t - w);
-                    p[v] = keep ? p[v] : 0.f;
+                    ds[v] = p[v] * (dp[v] - dvv[v >> 2][v & 3]);
+                    colsum += ds[v];
                 }
+                bf16x8 pf[2], dsf[2];
+                acc_to_bfrag(p, pf);
+                acc_to_bfrag(ds, dsf);
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
+                        dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
+                    }
             }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                ds[v] = p[v] * (dp[v] - dvv[v >> 2][v & 3]);
-                colsum += ds[v];
-            }
-            bf16x8 pf[2], dsf[2];
-            acc_to_bfrag(p, pf);
-            acc_to_bfrag(ds, dsf);
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
-                    dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
-                }
+            if (i < i_hi) store_vec(buf ^ 1);
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
+            __syncthreads();
         }
-        if (i < i_hi) store_vec(buf ^ 1);
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
-        __syncthreads();
-    }
 
-    const float cs = xhalf_sum(colsum);
+        const float cs = xhalf_sum(colsum);
+        if (key < N && h == 0) dc_col[(size_t)bh * N + key] = cs;
+    }  // query heads of the group
+
     if (key < N) {
         bf16_t* dkrow = dK + head_off + (size_t)key * D;
         bf16_t* dvrow = dV + head_off + (size_t)key * D;
@@ -220,7 +228,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(k4, bf16x4);
                 *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(v4, bf16x4);
             }
-        if (h == 0) dc_col[(size_t)bh * N + key] = cs;
     }
 }
 
@@ -238,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
     const float* __restrict__ Dv, bf16_t* __restrict__ dQ, float* __restrict__ dc_row, int N, int w,
-    float scale, int num_qtiles, int total_tiles) {
+    float scale, int num_qtiles, int total_tiles, int H, int G) {
     constexpr int BR = 128;
     constexpr int KC = D / 16, DB = D / 32;
     __shared__ DqSmem<D> sm;
@@ -253,8 +260,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     const float inv_scale = 1.0f / scale;
 
     const size_t head_off = (size_t)bh * N * D;
-    const char* Kh = reinterpret_cast<const char*>(K + head_off);
-    const char* Vh = reinterpret_cast<const char*>(V + head_off);
+    const size_t kv_off = (size_t)kv_head_of(bh, H, G) * N * D;
+    const char* Kh = reinterpret_cast<const char*>(K + kv_off);
+    const char* Vh = reinterpret_cast<const char*>(V + kv_off);
     const float* ch = c + (size_t)bh * N;
     const float cbase = ch[q0];
 
@@ -369,7 +377,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
 template <int D>
 static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                              const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                             float* ws, int B, int H, int N, int w, float scale, hipStream_t s) {
+                             float* ws, int B, int H, int Hkv, int N, int w, float scale, hipStream_t s) {
     const size_t rows = (size_t)B * H * N;
     const size_t pad = ((rows * sizeof(float) + 255) & ~(size_t)255) / sizeof(float);
     float* Dv = ws;
@@ -385,16 +393,16 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     const int nk = (N + 127) / 128;
     {
         ProfScope prof(kKernDkv, s);
-        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * H * nk), dim3(kThreads), 0, s,
+        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(kThreads), 0, s,
                            (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
-                           (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * H * nk);
+                           (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
     }
     const int nq = (N + 127) / 128;
     {
         ProfScope prof(kKernDq, s);
         hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads), 0, s,
                            (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
-                           (bf16_t*)dQ, dc_row, N, w, scale, nq, B * H * nq);
+                           (bf16_t*)dQ, dc_row, N, w, scale, nq, B * H * nq, H, H / Hkv);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -403,9 +411,9 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
 
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                          const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                         float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s) {
-    if (d == 128) return launch_bwd<128>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, w, scale, s);
-    return launch_bwd<64>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, N, w, scale, s);
+                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s) {
+    if (d == 128) return launch_bwd<128>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, w, scale, s);
+    return launch_bwd<64>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, w, scale, s);
 }
 
 }  // namespace gfwa

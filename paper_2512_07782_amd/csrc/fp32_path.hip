@@ -36,7 +36,7 @@ __device__ __forceinline__ float dot_row(const float* __restrict__ a_lds, const 
 __global__ __launch_bounds__(64 * kF32Waves) void fwd_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ c, float* __restrict__ O, float* __restrict__ L, int N, int D, int w,
-    float scale) {
+    float scale, int H, int G) {
     __shared__ float qs[kF32Waves][128];
     __shared__ float ps[kF32Waves][64];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -45,8 +45,9 @@ __global__ __launch_bounds__(64 * kF32Waves) void fwd_f32_kernel(
     const int t = (blockIdx.x % rows_per_head) * kF32Waves + wv;
     if (t >= N) return;  // whole wave leaves; no workgroup barriers are used below
     const size_t ho = (size_t)bh * N * D;
-    const float* Kh = K + ho;
-    const float* Vh = V + ho;
+    const size_t kvo = (size_t)kv_head_of(bh, H, G) * N * D;
+    const float* Kh = K + kvo;
+    const float* Vh = V + kvo;
     const float* ch = c + (size_t)bh * N;
     for (int x = lane; x < D; x += 64) qs[wv][x] = Q[ho + (size_t)t * D + x];
     const float ct = ch[t];
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void bwd_dq_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
     const float* __restrict__ Dv, float* __restrict__ dQ, float* __restrict__ dc_row, int N, int D,
-    int w, float scale) {
+    int w, float scale, int H, int G) {
     __shared__ float qs[kF32Waves][128];
     __shared__ float gs[kF32Waves][128];
     __shared__ float ds_s[kF32Waves][64];
@@ -106,8 +107,9 @@ __global__ __launch_bounds__(64 * kF32Waves) void bwd_dq_f32_kernel(
     const int t = (blockIdx.x % rows_per_head) * kF32Waves + wv;
     if (t >= N) return;
     const size_t ho = (size_t)bh * N * D;
-    const float* Kh = K + ho;
-    const float* Vh = V + ho;
+    const size_t kvo = (size_t)kv_head_of(bh, H, G) * N * D;
+    const float* Kh = K + kvo;
+    const float* Vh = V + kvo;
     const float* ch = c + (size_t)bh * N;
     for (int x = lane; x < D; x += 64) {
         qs[wv][x] = Q[ho + (size_t)t * D + x];
@@ -141,79 +143,88 @@ __global__ __launch_bounds__(64 * kF32Waves) void bwd_dq_f32_kernel(
     if (lane == 0) dc_row[(size_t)bh * N + t] = rs;
 }
 
-// ---- dK_i, dV_i and the column sum of dS
+// ---- dK_i, dV_i (summed over the G query heads that read this key/value head) and, per query
+// head, the column sum of dS
 __global__ __launch_bounds__(64 * kF32Waves) void bwd_dkv_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
     const float* __restrict__ Dv, float* __restrict__ dK, float* __restrict__ dV,
-    float* __restrict__ dc_col, int N, int D, int w, float scale) {
+    float* __restrict__ dc_col, int N, int D, int w, float scale, int H, int G) {
     __shared__ float ks[kF32Waves][128];
     __shared__ float vs[kF32Waves][128];
     __shared__ float p_s[kF32Waves][64];
     __shared__ float ds_s[kF32Waves][64];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int rows_per_head = (N + kF32Waves - 1) / kF32Waves;
-    const int bh = blockIdx.x / rows_per_head;
+    const int bkv = blockIdx.x / rows_per_head;  // flat key/value head
     const int i = (blockIdx.x % rows_per_head) * kF32Waves + wv;
     if (i >= N) return;
-    const size_t ho = (size_t)bh * N * D;
-    const float* Qh = Q + ho;
-    const float* Gh = dO + ho;
-    const float* ch = c + (size_t)bh * N;
-    const float* Lh = L + (size_t)bh * N;
-    const float* Dh = Dv + (size_t)bh * N;
+    const int Hkv = H / G;
+    const int bh0 = (bkv / Hkv) * H + (bkv % Hkv) * G;  // first query head of the group
+    const size_t kvo = (size_t)bkv * N * D;
     for (int x = lane; x < D; x += 64) {
-        ks[wv][x] = K[ho + (size_t)i * D + x];
-        vs[wv][x] = V[ho + (size_t)i * D + x];
+        ks[wv][x] = K[kvo + (size_t)i * D + x];
+        vs[wv][x] = V[kvo + (size_t)i * D + x];
     }
-    const float ci = ch[i];
     const long t_hi = min((long)N - 1, (long)i + w - 1);  // key i is seen by rows i .. i+w-1
-    float cs = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-    for (long t0 = i; t0 <= t_hi; t0 += 64) {
-        const long t = t0 + lane;
-        float p = 0.f, ds = 0.f;
-        if (t <= t_hi) {
-            const float s = fmaf(scale, dot_row(ks[wv], Qh + (size_t)t * D, D), ci - ch[t]);
-            p = expf(s - Lh[t]);
-            ds = p * (dot_row(vs[wv], Gh + (size_t)t * D, D) - Dh[t]);
-        }
-        cs += ds;
-        p_s[wv][lane] = p;
-        ds_s[wv][lane] = ds;
-        const int n = (int)min(64L, t_hi - t0 + 1);
-        for (int j = 0; j < n; ++j) {
-            const float pj = p_s[wv][j], dj = ds_s[wv][j];
-            const float* gr = Gh + (size_t)(t0 + j) * D;
-            const float* qr = Qh + (size_t)(t0 + j) * D;
-            v0 = fmaf(pj, gr[lane], v0);
-            k0 = fmaf(dj, qr[lane], k0);
-            if (D > 64) {
-                v1 = fmaf(pj, gr[lane + 64], v1);
-                k1 = fmaf(dj, qr[lane + 64], k1);
+    float k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+    for (int g = 0; g < G; ++g) {
+        const int bh = bh0 + g;
+        const size_t ho = (size_t)bh * N * D;
+        const float* Qh = Q + ho;
+        const float* Gh = dO + ho;
+        const float* ch = c + (size_t)bh * N;
+        const float* Lh = L + (size_t)bh * N;
+        const float* Dh = Dv + (size_t)bh * N;
+        const float ci = ch[i];
+        float cs = 0.f;
+        for (long t0 = i; t0 <= t_hi; t0 += 64) {
+            const long t = t0 + lane;
+            float p = 0.f, ds = 0.f;
+            if (t <= t_hi) {
+                const float s = fmaf(scale, dot_row(ks[wv], Qh + (size_t)t * D, D), ci - ch[t]);
+                p = expf(s - Lh[t]);
+                ds = p * (dot_row(vs[wv], Gh + (size_t)t * D, D) - Dh[t]);
+            }
+            cs += ds;
+            p_s[wv][lane] = p;
+            ds_s[wv][lane] = ds;
+            const int n = (int)min(64L, t_hi - t0 + 1);
+            for (int j = 0; j < n; ++j) {
+                const float pj = p_s[wv][j], dj = ds_s[wv][j];
+                const float* gr = Gh + (size_t)(t0 + j) * D;
+                const float* qr = Qh + (size_t)(t0 + j) * D;
+                v0 = fmaf(pj, gr[lane], v0);
+                k0 = fmaf(dj, qr[lane], k0);
+                if (D > 64) {
+                    v1 = fmaf(pj, gr[lane + 64], v1);
+                    k1 = fmaf(dj, qr[lane + 64], k1);
+                }
             }
         }
+        cs = wave_sum(cs);
+        if (lane == 0) dc_col[(size_t)bh * N + i] = cs;
     }
-    cs = wave_sum(cs);
-    dK[ho + (size_t)i * D + lane] = scale * k0;
-    dV[ho + (size_t)i * D + lane] = v0;
+    dK[kvo + (size_t)i * D + lane] = scale * k0;
+    dV[kvo + (size_t)i * D + lane] = v0;
     if (D > 64) {
-        dK[ho + (size_t)i * D + lane + 64] = scale * k1;
-        dV[ho + (size_t)i * D + lane + 64] = v1;
+        dK[kvo + (size_t)i * D + lane + 64] = scale * k1;
+        dV[kvo + (size_t)i * D + lane + 64] = v1;
     }
-    if (lane == 0) dc_col[(size_t)bh * N + i] = cs;
 }
 
 hipError_t forward_f32(const float* Q, const float* K, const float* V, const float* c, float* O, float* L,
-                       int B, int H, int N, int d, int w, float scale, hipStream_t s) {
+                       int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s) {
     const int blocks = B * H * ((N + kF32Waves - 1) / kF32Waves);
     ProfScope prof(kKernForward, s);
-    hipLaunchKernelGGL(fwd_f32_kernel, dim3(blocks), dim3(64 * kF32Waves), 0, s, Q, K, V, c, O, L, N, d, w, scale);
+    hipLaunchKernelGGL(fwd_f32_kernel, dim3(blocks), dim3(64 * kF32Waves), 0, s, Q, K, V, c, O, L, N, d, w, scale,
+                       H, H / Hkv);
     return hipGetLastError();
 }
 
 hipError_t backward_f32(const float* Q, const float* K, const float* V, const float* O, const float* dO,
                         const float* c, const float* L, float* dQ, float* dK, float* dV, float* dalpha,
-                        float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s) {
+                        float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s) {
     const size_t rows = (size_t)B * H * N;
     float* Dv = ws;
     float* dc_col = ws + rows;
@@ -227,13 +238,13 @@ hipError_t backward_f32(const float* Q, const float* K, const float* V, const fl
     }
     {
         ProfScope prof(kKernDkv, s);
-        hipLaunchKernelGGL(bwd_dkv_f32_kernel, dim3(blocks), dim3(64 * kF32Waves), 0, s, Q, K, V, dO, c, L,
-                           Dv, dK, dV, dc_col, N, d, w, scale);
+        hipLaunchKernelGGL(bwd_dkv_f32_kernel, dim3(B * Hkv * per_head), dim3(64 * kF32Waves), 0, s, Q, K, V, dO,
+                           c, L, Dv, dK, dV, dc_col, N, d, w, scale, H, H / Hkv);
     }
     {
         ProfScope prof(kKernDq, s);
         hipLaunchKernelGGL(bwd_dq_f32_kernel, dim3(blocks), dim3(64 * kF32Waves), 0, s, Q, K, V, dO, c, L,
-                           Dv, dQ, dc_row, N, d, w, scale);
+                           Dv, dQ, dc_row, N, d, w, scale, H, H / Hkv);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

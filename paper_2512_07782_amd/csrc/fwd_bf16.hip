@@ -60,7 +60,7 @@ template <int D>
 __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ c, bf16_t* __restrict__ O, float* __restrict__ L, int N, int w,
-    float scale_log2, int num_qtiles, int total_tiles) {
+    float scale_log2, int num_qtiles, int total_tiles, int H, int G) {
     constexpr int BR = kFwdBR;
     constexpr int KC = D / 16;  // MFMA k-chunks along the head dimension
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
@@ -95,8 +95,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         bh = tl / num_qtiles;
         q0 = (tl % num_qtiles) * BR;
         head_off = (size_t)bh * N * D;
-        Kh = reinterpret_cast<const char*>(K + head_off);
-        Vh = reinterpret_cast<const char*>(V + head_off);
+        const size_t kv_off = (size_t)kv_head_of(bh, H, G) * N * D;
+        Kh = reinterpret_cast<const char*>(K + kv_off);
+        Vh = reinterpret_cast<const char*>(V + kv_off);
         ch = c + (size_t)bh * N;
         cbase = ch[q0];
         // the two waves of a SIMD take adjacent 32-query slabs, so their bands differ by one block
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 
 template <int D>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const float* c, void* O,
-                             float* L, int B, int H, int N, int w, float scale, hipStream_t s) {
+                             float* L, int B, int H, int Hkv, int N, int w, float scale, hipStream_t s) {
     const int num_qtiles = (N + kFwdBR - 1) / kFwdBR;
     const int total = B * H * num_qtiles;
     static bool attr_set = false;
@@ -409,14 +410,14 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
     ProfScope prof(kKernForward, s);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(grid), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w,
-                       scale * kLog2e, num_qtiles, total);
+                       scale * kLog2e, num_qtiles, total, H, H / Hkv);
     return hipGetLastError();
 }
 
 hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
-                        int B, int H, int N, int d, int w, float scale, hipStream_t s) {
-    if (d == 128) return launch_fwd<128>(Q, K, V, c, O, L, B, H, N, w, scale, s);
-    return launch_fwd<64>(Q, K, V, c, O, L, B, H, N, w, scale, s);
+                        int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s) {
+    if (d == 128) return launch_fwd<128>(Q, K, V, c, O, L, B, H, Hkv, N, w, scale, s);
+    return launch_fwd<64>(Q, K, V, c, O, L, B, H, Hkv, N, w, scale, s);
 }
 
 }  // namespace gfwa

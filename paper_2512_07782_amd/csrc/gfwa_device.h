@@ -6,6 +6,12 @@
 
 namespace gfwa {
 
+// Grouped-query layout: query head (b, h), flat index bh = b * H + h, reads the keys and values of
+// head h / G of the B x (H / G) key/value heads; returns that head's flat index.  G = 1: bh itself.
+__device__ __forceinline__ int kv_head_of(int bh, int H, int G) {
+    return G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G;
+}
+
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));

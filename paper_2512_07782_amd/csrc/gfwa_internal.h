@@ -15,18 +15,20 @@ hipError_t gate_activation_backward(const float* hpre, const float* beta, float 
 hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
                           hipStream_t s);
 
+// Q, O, dO, dQ: [B,H,N,d]; K, V, dK, dV: [B,Hkv,N,d] with Hkv dividing H (query head h reads head h / (H/Hkv));
+// c, L, dalpha: [B,H,N].
 hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float* c, void* O, float* L,
-                        int B, int H, int N, int d, int w, float scale, hipStream_t s);
+                        int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 hipError_t forward_f32(const float* Q, const float* K, const float* V, const float* c, float* O,
-                       float* L, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+                       float* L, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 
 // Workspace layout of the backward: three fp32 vectors of B*H*N: D, dc_col, dc_row.
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                          const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                         float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 hipError_t backward_f32(const float* Q, const float* K, const float* V, const float* O, const float* dO,
                         const float* c, const float* L, float* dQ, float* dK, float* dV, float* dalpha,
-                        float* ws, int B, int H, int N, int d, int w, float scale, hipStream_t s);
+                        float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
 enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,

@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
-                            "gfwa_forward", "gfwa_backward_workspace_bytes",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
     for n in names:
@@ -62,6 +62,11 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_gate_activation_prefix(good, good, f, P(0x1002), 1, 1, 8, None) == -4
     assert lib.gfwa_gate_activation_backward(good, good, f, good, good, None, 1, 1, 8, None) == -1
     assert lib.gfwa_gate_activation_backward(good, good, f, good, good, good, 1, 0, 8, None) == -2
+    # grouped-query calls: the number of key/value heads must divide the number of query heads
+    assert lib.gfwa_forward_gqa(0, good, good, good, good, good, good, 1, 6, 4, 64, 128, 16, f, None) == -2
+    assert lib.gfwa_forward_gqa(0, good, good, good, good, good, good, 1, 6, 0, 64, 128, 16, f, None) == -2
+    assert lib.gfwa_backward_gqa(0, good, good, good, good, good, good, good, good, good, good, good, good,
+                                 1 << 20, 1, 6, 5, 64, 128, 16, f, None) == -2
     # forward
     args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
                          kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]

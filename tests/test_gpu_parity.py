@@ -403,6 +403,83 @@ def test_forward_backward_bf16_mid_size(g, oracle, B, H, N, d, w, heads):
     check_grads(got, ref, 1e-2, "mid")
 
 
+# ------------------------------------------------------------------------------------------
+# grouped-query layout
+# ------------------------------------------------------------------------------------------
+def run_gqa(g, oracle, wl, groups=None):
+    """Forward + backward of a grouped-query workload on the GPU and in the oracle.  `groups`: flat
+    key/value head indices (b * Hkv + kv) whose results are compared (all when None)."""
+    G = wl.H // wl.Hkv
+    ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha", "dO")}
+    c32 = oracle.gate_prefix(ins["alpha"]).astype(np.float32)
+    Qd, Kd, Vd, dOd = (dev(ins[t], wl.dtype) for t in ("Q", "K", "V", "dO"))
+    cd = dev(c32, "f32")
+    Od, Ld = g.gfwa_forward_gqa(Qd, Kd, Vd, cd, wl.w, wl.scale)
+    dQ, dK, dV, dalpha = g.gfwa_backward_gqa(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale)
+    torch.cuda.synchronize()
+    assert dK.shape == Kd.shape and dV.shape == Vd.shape
+    if groups is None:
+        groups = list(range(wl.B * wl.Hkv))
+    qheads = [(kv // wl.Hkv) * wl.H + (kv % wl.Hkv) * G + j for kv in groups for j in range(G)]
+    # the selected groups as a batch of their own: [len(groups), G, N, d] queries on [len(groups), 1, N, d] keys
+    shp_q = (len(groups), G, wl.N, wl.d)
+    shp_k = (len(groups), 1, wl.N, wl.d)
+    sq = lambda x: oracle.select_heads(x, qheads, 2).reshape(shp_q)
+    sk = lambda x: oracle.select_heads(x, groups, 2).reshape(shp_k)
+    sv = lambda x: oracle.select_heads(x, qheads, 1).reshape(shp_q[:3])
+    O_ref, L_ref = oracle.forward_gqa_from_c(sq(ins["Q"]), sk(ins["K"]), sk(ins["V"]), sv(c32), wl.w, wl.scale)
+    ref = oracle.backward_gqa_from_c(sq(ins["Q"]), sk(ins["K"]), sk(ins["V"]), sv(c32), sq(ins["dO"]), wl.w, wl.scale)
+    got = {"O": sq(host(Od)), "L": sv(host(Ld)), "dQ": sq(host(dQ)), "dK": sk(host(dK)), "dV": sk(host(dV)),
+           "dalpha": sv(host(dalpha))}
+    ref.update({"O": O_ref, "L": L_ref})
+    LAST["c_span"] = float(c32.max())
+    return got, ref
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,w", [(1, 4, 2, 77, 64, 9), (2, 6, 2, 130, 128, 500), (1, 4, 1, 65, 64, 1)])
+def test_gqa_f32(g, oracle, B, H, Hkv, N, d, w):
+    note("gqa f32", B, H, Hkv, N, d, w)
+    wl = gi.custom("gqa32", B, H, N, d, w, "f32", alpha_mu=-1.0, index=13, backward=True, kv_heads=Hkv)
+    got, ref = run_gqa(g, oracle, wl)
+    assert rel_inf(got["O"], ref["O"]) <= 1e-5
+    assert (np.abs(got["L"] - ref["L"]) <= 1e-5 * np.abs(ref["L"]).max() + 1e-5).all()
+    check_grads(got, ref, 1e-5, "gqa f32")
+
+
+GQA_BF16 = [(1, 4, 1, 300, 128, 64), (2, 8, 2, 515, 64, 512), (1, 4, 2, 1536, 128, 1024), (1, 8, 2, 2050, 64, 700),
+            (1, 2, 1, 37, 64, 5), (1, 3, 1, 4099, 128, 300)]
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,w", GQA_BF16)
+def test_gqa_bf16(g, oracle, B, H, Hkv, N, d, w):
+    note("gqa bf16", B, H, Hkv, N, d, w)
+    wl = gi.custom("gqa16", B, H, N, d, w, "bf16", alpha_mu=-1.0, index=14, backward=True, kv_heads=Hkv)
+    got, ref = run_gqa(g, oracle, wl)
+    check_bf16_forward(got["O"], got["L"], ref["O"], ref["L"], tag="gqa")
+    check_grads(got, ref, 1e-2, "gqa bf16")
+
+
+@pytest.mark.parametrize("name,groups", [("lm_gqa_bwd", [0, 7, 15]), ("long_gqa_bwd", [3])])
+def test_gqa_bf16_full_size(g, oracle, name, groups):
+    note("gqa full size", name, groups)
+    got, ref = run_gqa(g, oracle, gi.WORKLOADS[name], groups=groups)
+    check_bf16_forward(got["O"], got["L"], ref["O"], ref["L"], tag=name)
+    check_grads(got, ref, 1e-2, name)
+
+
+def test_gqa_with_one_head_per_group_is_the_plain_call(g, oracle):
+    wl = gi.custom("gqa1", 2, 3, 700, 128, 200, "bf16", alpha_mu=-1.0, index=14, backward=True)
+    ins = {t: dev(gi.make_tensor(wl, t), "bf16") for t in ("Q", "K", "V", "dO")}
+    cd = g.gfwa_gate_prefix(dev(gi.make_tensor(wl, "alpha"), "f32"))
+    O1, L1 = g.gfwa_forward(ins["Q"], ins["K"], ins["V"], cd, wl.w, wl.scale)
+    O2, L2 = g.gfwa_forward_gqa(ins["Q"], ins["K"], ins["V"], cd, wl.w, wl.scale)
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    r1 = g.gfwa_backward(ins["Q"], ins["K"], ins["V"], O1, ins["dO"], cd, L1, wl.w, wl.scale)
+    r2 = g.gfwa_backward_gqa(ins["Q"], ins["K"], ins["V"], O1, ins["dO"], cd, L1, wl.w, wl.scale)
+    for a, b in zip(r1, r2):
+        assert torch.equal(a, b)
+
+
 def test_forward_is_deterministic(g, oracle):
     wl = gi.custom("detf", 1, 2, 1500, 128, 700, "bf16", alpha_mu=-1.0, index=15)
     ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha")}
