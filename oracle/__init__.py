@@ -204,6 +204,35 @@ def backward_gqa_from_c(Q, K, V, c, dO, w: int, scale: float) -> Dict[str, np.nd
     return out
 
 
+# --------------------------------------------------------------------------
+# decoding step with a key/value cache (Sec. 1: O(wd) work per generated token).  It is row `pos` of
+# the forward definition, written out directly: one query per (b, h) against the cached keys and
+# values of positions max(0, pos-w+1) .. pos.
+# --------------------------------------------------------------------------
+def decode_from_c(q, Kc, Vc, c, pos, w: int, scale: float):
+    """o [B,H,d], L [B,H] for q [B,H,d], caches Kc, Vc [B,Hkv,T,d], prefix c [B,H,T] (c[..., pos] included)
+    and the current position pos[b] of every batch entry."""
+    q, Kc, Vc, c = _f64(q), _f64(Kc), _f64(Vc), _f64(c)
+    B, H, d = q.shape
+    Hkv = Kc.shape[1]
+    assert H % Hkv == 0 and c.shape[:2] == (B, H) and c.shape[2] == Kc.shape[2]
+    G = H // Hkv
+    o = np.empty((B, H, d))
+    L = np.empty((B, H))
+    for b in range(B):
+        p = int(pos[b])
+        lo = max(0, p - int(w) + 1)
+        for h in range(H):
+            K = Kc[b, h // G, lo:p + 1]
+            V = Vc[b, h // G, lo:p + 1]
+            s = scale * (K @ q[b, h]) + (c[b, h, lo:p + 1] - c[b, h, p])
+            m = s.max()
+            e = np.exp(s - m)
+            L[b, h] = m + np.log(e.sum())
+            o[b, h] = (e / e.sum()) @ V
+    return o, L
+
+
 def dalpha_direct(dS_band, w: int) -> np.ndarray:
     """d(alpha) from the band of dS without going through dc (tiny N only)."""
     lib = _load()
