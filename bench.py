@@ -58,6 +58,54 @@ def gate_only(args, g, torch) -> int:
     return 0
 
 
+def decode_only(args, g, torch) -> int:
+    """The decoding step alone: HBM-bound on reading the window of the key/value cache once."""
+    B, H, Hkv, T, d, w = (int(x) for x in args.decode.split(","))
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev).manual_seed(2)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=gen)
+    q = rnd(B, H, d).to(torch.bfloat16)
+    Kc, Vc = rnd(B, Hkv, T, d).to(torch.bfloat16), rnd(B, Hkv, T, d).to(torch.bfloat16)
+    c = torch.cumsum(torch.nn.functional.softplus(rnd(B, H, T) - 2.0), dim=-1)
+    alpha_t = torch.nn.functional.softplus(rnd(B, H) - 2.0)
+    pos = torch.full((B,), T - 1, dtype=torch.int32, device=dev)
+    o = torch.empty_like(q)
+    L = torch.empty(B, H, dtype=torch.float32, device=dev)
+    ws = torch.empty(g.gfwa_decode_workspace_bytes(B, H, T, d, w), dtype=torch.uint8, device=dev)
+    n = min(w, T)
+    # bytes one step has to move: the window of K and V once per key/value head, the window of c once per
+    # query head, the query, the output and L
+    algo = B * Hkv * n * d * 2 * 2 + B * H * n * 4 + B * H * (2 * d * 2 + 8)
+
+    def step():
+        g.gfwa_decode(q, Kc, Vc, c, pos, w, 1.0 / d ** 0.5, alpha_t=alpha_t, o=o, L=L, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    g.gfwa_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    g.gfwa_profile_enable(False)
+    prof = {k: v for k, v in g.gfwa_profile_read().items() if v[1]}
+    part_ms = prof["decode_partial"][0] / prof["decode_partial"][1]
+    comb_ms = prof["decode_combine"][0] / prof["decode_combine"][1]
+    gbs = algo / part_ms / 1e6
+    print(json.dumps({
+        "metric": "GatedFWA decoding step, algorithmic GB/s of the cache-reading kernel", "value": round(gbs, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"decode: B={B} H={H} Hkv={Hkv} T={T} d={d} w={w} bf16 cache, all positions T-1"},
+        "roofline": {"kernel": "decode_partial", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
+        "detail": {"decode_partial_ms": round(part_ms, 5), "decode_combine_ms": round(comb_ms, 5),
+                   "algorithmic_bytes": algo, "tokens_per_s": round(B / (wall_ms * 1e-3), 1)}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +129,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="before the warm-up, copy this many MiB once with a plain elementwise copy "
                          "kernel (the known-size reference the traffic counters are scaled by)")
+    ap.add_argument("--decode", default=None, metavar="B,H,Hkv,T,d,w",
+                    help="time the decoding step (one query per head against the cached window, bf16 cache, every "
+                         "sequence at position T-1) and print its GB/s on the window's bytes instead of the usual "
+                         "line, e.g. 64,32,8,16384,128,1024")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no inter-GPU part); "
@@ -100,6 +152,8 @@ def main() -> int:
     dev = "cuda:0"
     if args.gate_only:
         return gate_only(args, g, torch)
+    if args.decode:
+        return decode_only(args, g, torch)
     wl = gi.WORKLOADS[args.workload]
     ins = {t: gi.make_tensor(wl, t) for t in ("Q", "K", "V", "alpha", "dO")} if wl.backward else gi.make_inputs(wl)
     bf = wl.dtype == "bf16"

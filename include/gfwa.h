@@ -134,6 +134,30 @@ int gfwa_backward_gqa(gfwa_dtype_t dt, const void *Q, const void *K, const void 
                       float *dalpha, void *workspace, size_t workspace_bytes, int B, int H, int Hkv,
                       int N, int d, int w, float scale, gfwa_stream_t stream);
 
+/*
+ * Decoding step with a key/value cache (paper Sec. 1: with a KV cache the method costs O(wd) per
+ * generated token; the arithmetic is row `pos` of the forward, Sec. 3.2 / Alg. 2).  For every batch
+ * entry b with current position p = pos[b] and every query head h (grouped-query layout as above):
+ *
+ *   S_i = scale * <q, k_i> + (c_i - c_p)        for  max(0, p-w+1) <= i <= p
+ *   o   = sum_i softmax_i(S_i) v_i              L = log sum_i exp(S_i)
+ *
+ * q: [B,H,d] of dtype `dt`, the new token's query.  Kc, Vc: [B,Hkv,T,d] of dtype `dt`, the caches; rows
+ * 0..p of entry b must hold the keys and values of positions 0..p (the caller appends row p before
+ * the call); rows past p are not read.  pos: [B] int32 in device memory, 0 <= pos[b] < T (a value
+ * outside is clamped into the range).  c: [B,H,T] fp32 gate prefix.  If alpha_t ([B,H] fp32, the new
+ * token's gate) is not NULL the call advances the prefix itself, c[b,h,p] = c[b,h,p-1] + alpha_t[b,h]
+ * (c[b,h,-1] = 0), stores it and uses it; with alpha_t == NULL, c[b,h,p] must already be there.
+ * o: [B,H,d] of dtype `dt`, out.  L: [B,H] fp32 out, may be NULL.  workspace: device scratch of at least
+ * gfwa_decode_workspace_bytes(...) bytes, 16-byte aligned, contents undefined before and after.
+ * Only the window is read: 2 * min(w, p+1) * d cache elements per key/value head.
+ */
+size_t gfwa_decode_workspace_bytes(int B, int H, int T, int d, int w);
+int gfwa_decode(gfwa_dtype_t dt, const void *q, const void *Kc, const void *Vc, float *c,
+                const float *alpha_t, const int *pos, void *o, float *L, void *workspace,
+                size_t workspace_bytes, int B, int H, int Hkv, int T, int d, int w, float scale,
+                gfwa_stream_t stream);
+
 /* Static, human-readable text for a status code (for GFWA_ERR_HIP: the last HIP error text). */
 const char *gfwa_strerror(int code);
 
@@ -144,10 +168,11 @@ int gfwa_version(void);
  * Instrumentation (not part of the method): per-kernel timing with HIP events recorded on the
  * caller's stream around every kernel the library launches.  gfwa_profile_enable(1) clears the
  * records and starts recording (at most 8192 launches are kept), gfwa_profile_enable(0) stops.
- * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 8), the
- * summed duration in milliseconds and the number of launches; n must be >= 8.  Kernel ids:
+ * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 10), the
+ * summed duration in milliseconds and the number of launches; n must be >= 10.  Kernel ids:
  * 0 gate prefix scan, 1 forward, 2 backward row-dot (D), 3 backward dK/dV, 4 backward dQ,
- * 5 gate-gradient reverse scan, 6 gate activation + prefix scan, 7 gate activation backward;
+ * 5 gate-gradient reverse scan, 6 gate activation + prefix scan, 7 gate activation backward,
+ * 8 decoding step (per-chunk partials), 9 decoding step (merge of the chunks);
  * gfwa_profile_kernel_name gives the same as text.
  * Not thread-safe; host memory only.
  */

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     gfwa_backward,
     gfwa_backward_gqa,
     gfwa_backward_workspace_bytes,
+    gfwa_decode,
+    gfwa_decode_workspace_bytes,
     gfwa_forward,
     gfwa_forward_gqa,
     gfwa_gate_activation_backward,

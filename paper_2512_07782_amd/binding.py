@@ -19,10 +19,10 @@ _lib: Optional[ctypes.CDLL] = None
 GFWA_BF16, GFWA_F32 = 0, 1
 
 EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
-           "gfwa_forward_gqa", "gfwa_backward_gqa",
+           "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
-N_KERNELS = 8
+N_KERNELS = 10
 
 
 class GfwaError(RuntimeError):
@@ -63,6 +63,10 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_backward_gqa.argtypes = [i, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, ctypes.c_size_t,
                                       i, i, i, i, i, i, f, vp]
     lib.gfwa_backward_gqa.restype = i
+    lib.gfwa_decode_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.gfwa_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.gfwa_decode.argtypes = [i, vp, vp, vp, fp, fp, vp, vp, fp, vp, ctypes.c_size_t, i, i, i, i, i, i, f, vp]
+    lib.gfwa_decode.restype = i
     lib.gfwa_strerror.argtypes = [i]
     lib.gfwa_strerror.restype = ctypes.c_char_p
     lib.gfwa_version.argtypes = []
@@ -286,6 +290,48 @@ def gfwa_backward_gqa(Q, K, V, O, dO, c, L, w: int, scale: float, workspace: Opt
                                             workspace.data_ptr(), ws_bytes, B, H, Hkv, N, d, int(w),
                                             float(scale), _stream()))
     return dQ, dK, dV, dalpha
+
+
+def gfwa_decode_workspace_bytes(B: int, H: int, T: int, d: int, w: int) -> int:
+    return int(load_library().gfwa_decode_workspace_bytes(B, H, T, d, int(w)))
+
+
+def gfwa_decode(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: torch.Tensor, pos: torch.Tensor, w: int,
+                scale: float, alpha_t: Optional[torch.Tensor] = None, o: Optional[torch.Tensor] = None,
+                L: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """One decoding step: q [B,H,d] against the caches Kc, Vc [B,Hkv,T,d] at positions pos [B] (int32);
+    c [B,H,T] fp32 (entry pos is written when alpha_t [B,H] is given).  Returns o [B,H,d], L [B,H]."""
+    if q.dim() != 3 or Kc.dim() != 4:
+        raise ValueError("q must be [B,H,d] and Kc [B,Hkv,T,d]")
+    B, H, d = q.shape
+    Hkv, T = Kc.shape[1], Kc.shape[2]
+    if Hkv <= 0 or H % Hkv != 0:
+        raise ValueError(f"the number of key/value heads ({Hkv}) must divide the number of query heads ({H})")
+    dt = _dt(q)
+    _need(q, (B, H, d), q.dtype, "q")
+    for name, t in (("Kc", Kc), ("Vc", Vc)):
+        _need(t, (B, Hkv, T, d), q.dtype, name)
+    _need(c, (B, H, T), torch.float32, "c")
+    _need(pos, (B,), torch.int32, "pos")
+    if alpha_t is not None:
+        _need(alpha_t, (B, H), torch.float32, "alpha_t")
+    if o is None:
+        o = torch.empty_like(q)
+    if L is None:
+        L = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    _need(o, (B, H, d), q.dtype, "o")
+    _need(L, (B, H), torch.float32, "L")
+    need = gfwa_decode_workspace_bytes(B, H, T, d, w)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _check(load_library().gfwa_decode(dt, q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), c.data_ptr(),
+                                      alpha_t.data_ptr() if alpha_t is not None else None, pos.data_ptr(),
+                                      o.data_ptr(), L.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), B, H, Hkv, T, d, int(w),
+                                      float(scale), _stream()))
+    return o, L
 
 
 def gfwa_profile_enable(on: bool) -> None:

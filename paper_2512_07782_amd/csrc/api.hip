@@ -152,6 +152,27 @@ int gfwa_backward_gqa(gfwa_dtype_t dt, const void* Q, const void* K, const void*
         backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, d, w, scale, stream));
 }
 
+size_t gfwa_decode_workspace_bytes(int B, int H, int T, int d, int w) {
+    if (check_dims(B, H, T, d, w, true) != GFWA_OK) return 0;
+    return (decode_workspace_bytes(B, H, T, d, w) + 255) & ~(size_t)255;
+}
+
+int gfwa_decode(gfwa_dtype_t dt, const void* q, const void* Kc, const void* Vc, float* c, const float* alpha_t,
+                const int* pos, void* o, float* L, void* workspace, size_t workspace_bytes, int B, int H, int Hkv,
+                int T, int d, int w, float scale, gfwa_stream_t stream) {
+    if (!q || !Kc || !Vc || !c || !pos || !o) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, T, d, w, true)) return r;
+    if (Hkv <= 0 || H % Hkv != 0) return GFWA_ERR_DIM;
+    if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
+    if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(o, 16) || !aligned(c, 4) ||
+        !aligned(pos, 4) || (alpha_t && !aligned(alpha_t, 4)) || (L && !aligned(L, 4)))
+        return GFWA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < gfwa_decode_workspace_bytes(B, H, T, d, w)) return GFWA_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return GFWA_ERR_ALIGN;
+    return hip_status(decode(dt == GFWA_BF16, q, Kc, Vc, c, alpha_t, pos, o, L, (float*)workspace, B, H, Hkv, T, d,
+                             w, scale, stream));
+}
+
 const char* gfwa_strerror(int code) {
     switch (code) {
         case GFWA_OK: return "ok";
@@ -159,7 +180,7 @@ const char* gfwa_strerror(int code) {
         case GFWA_ERR_DIM: return "invalid size: B, H, N, d must be > 0, w >= 1, Hkv > 0 dividing H, within index range";
         case GFWA_ERR_UNSUPPORTED: return "unsupported head dimension (64 or 128) or dtype";
         case GFWA_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes matrices, 4 bytes vectors)";
-        case GFWA_ERR_WORKSPACE: return "workspace missing or smaller than gfwa_backward_workspace_bytes()";
+        case GFWA_ERR_WORKSPACE: return "workspace missing or smaller than gfwa_backward_workspace_bytes() / gfwa_decode_workspace_bytes()";
         case GFWA_ERR_HIP: return g_hip_msg;
         default: return "unknown status code";
     }
@@ -194,7 +215,7 @@ int gfwa_profile_read(float* total_ms, int* launches, int n) {
 const char* gfwa_profile_kernel_name(int k) {
     static const char* names[kKernCount] = {"gate_prefix_scan", "forward", "bwd_rowdot", "bwd_dkv", "bwd_dq",
                                             "gate_grad_scan", "gate_activation_prefix_scan",
-                                            "gate_activation_bwd"};
+                                            "gate_activation_bwd", "decode_partial", "decode_combine"};
     return (k >= 0 && k < kKernCount) ? names[k] : "";
 }
 

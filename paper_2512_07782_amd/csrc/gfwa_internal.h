@@ -30,9 +30,16 @@ hipError_t backward_f32(const float* Q, const float* K, const float* V, const fl
                         const float* c, const float* L, float* dQ, float* dK, float* dV, float* dalpha,
                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 
+// Decoding step: q, o [B,H,d]; caches Kc, Vc [B,Hkv,T,d]; c [B,H,T] (entry pos[b] written when alpha_t is
+// given); pos [B] device ints; part: decode_workspace_bytes() of scratch.
+size_t decode_workspace_bytes(int B, int H, int Tlen, int d, int w);
+hipError_t decode(bool bf16, const void* q, const void* Kc, const void* Vc, float* c, const float* alpha_t,
+                  const int* pos, void* o, float* L, float* part, int B, int H, int Hkv, int Tlen, int d, int w,
+                  float scale, hipStream_t s);
+
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
 enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,
-                kKernGateActBwd, kKernCount };
+                kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernCount };
 
 // RAII pair of HIP events around one kernel launch on stream s; a no-op unless profiling is on.
 struct ProfScope {

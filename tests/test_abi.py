@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
-                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
     for n in names:
@@ -67,6 +67,18 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_forward_gqa(0, good, good, good, good, good, good, 1, 6, 0, 64, 128, 16, f, None) == -2
     assert lib.gfwa_backward_gqa(0, good, good, good, good, good, good, good, good, good, good, good, good,
                                  1 << 20, 1, 6, 5, 64, 128, 16, f, None) == -2
+    # decoding step
+    dec = lambda **kw: [0, kw.get("q", good), good, good, good, None, kw.get("pos", good), good, None,
+                        kw.get("ws", good), kw.get("wsb", 1 << 20), 1, kw.get("H", 4), kw.get("Hkv", 2), 64,
+                        kw.get("d", 128), 16, f, None]
+    assert lib.gfwa_decode(*dec(q=None)) == -1
+    assert lib.gfwa_decode(*dec(pos=None)) == -1
+    assert lib.gfwa_decode(*dec(Hkv=3)) == -2
+    assert lib.gfwa_decode(*dec(d=96)) == -3
+    assert lib.gfwa_decode(*dec(ws=None)) == -5
+    assert lib.gfwa_decode(*dec(wsb=16)) == -5
+    assert lib.gfwa_decode_workspace_bytes(2, 4, 1000, 128, 300) == (2 * 4 * 2 * 130 * 4 + 255) // 256 * 256   # two chunks of 256 keys
+    assert lib.gfwa_decode_workspace_bytes(2, 4, 1000, 96, 300) == 0
     # forward
     args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
                          kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]
