@@ -69,6 +69,33 @@ def test_decode_matches_oracle(g, oracle, B, H, Hkv, T, d, w, dtype):
     assert (lerr <= 1e-4 + 1e-5 * np.abs(L_ref) + 2.0 ** -21 * float(c32.max())).all()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,H,Hkv,T,d,w", [(2, 8, 2, 700, 128, 512), (2, 4, 2, 900, 64, 300), (1, 4, 4, 640, 128, 640)])
+def test_decode_with_scores_far_apart(g, oracle, B, H, Hkv, T, d, w, dtype):
+    # queries and keys of large norm: scores differ by far more than 2^60 inside a wave's 64 keys, so the
+    # exponentials cannot all be taken against the score of the newest key (the reference must be raised)
+    wl = gi.custom("decbig", B, H, T, d, w, dtype, alpha_mu=-1.0, index=25, kv_heads=Hkv, qkv_std=4.0)
+    Kc, Vc, alpha = (gi.make_tensor(wl, t) for t in ("K", "V", "alpha"))
+    q = np.ascontiguousarray(gi.make_tensor(wl, "Q")[:, :, 0, :])
+    # one early key of the window aligned with the query of head 0: by far the largest score
+    pos = np.full(B, T - 1, dtype=np.int32)
+    Kc[:, 0, T - 40, :] = q[:, 0, :]
+    c32 = oracle.gate_prefix(alpha).astype(np.float32)
+    o, L = g.gfwa_decode(dev(q, dtype), dev(Kc, dtype), dev(Vc, dtype), dev(c32, "f32"), dev(pos, "i32"), w, wl.scale)
+    torch.cuda.synchronize()
+    o_ref, L_ref = oracle.decode_from_c(q, Kc, Vc, c32, pos, w, wl.scale)
+    spread = wl.scale * np.abs(np.einsum("bhd,bhd->bh", q, q)).max()
+    print(f"  largest score about {spread:.0f} nats", flush=True)
+    assert spread > 100
+    err = np.abs(host(o) - o_ref)
+    assert np.isfinite(host(o)).all() and np.isfinite(host(L)).all()
+    if dtype == "bf16":
+        assert err.max() <= 4 * 2e-2 and err.mean() <= 4 * 2e-3          # values are 4 times larger here
+    else:
+        assert err.max() <= 1e-5 * np.abs(o_ref).max()
+    assert (np.abs(host(L) - L_ref) <= 1e-4 + 1e-5 * np.abs(L_ref) + 2.0 ** -21 * float(c32.max())).all()
+
+
 @pytest.mark.parametrize("B,H,Hkv,T,d,w", [(3, 8, 2, 300, 128, 64), (2, 4, 1, 1000, 64, 333)])
 def test_decode_advances_the_gate_prefix(g, oracle, B, H, Hkv, T, d, w):
     wl, q, Kc, Vc, alpha, pos = make_case(B, H, Hkv, T, d, w, "bf16", 22)
