@@ -57,7 +57,7 @@ template <int D>
 struct DkvSmem {
     TilePairSmem<D> qg;                    // a = Q tile, b = dO tile
     alignas(16) float nl[2][kTileRows];    // -(L_t + c_t - c_base) / scale; -big for rows >= N
-    alignas(16) float dvec[2][kTileRows];  // D_t
+    alignas(16) float dvec[2][kTileRows];  // -D_t
 };
 
 template <int D>
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 const int t = i * kTileRows + tid;
                 if (t < N) {
                     nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
-                    d_stage = Dh[t];
+                    d_stage = -Dh[t];
                 } else {
                     nl_stage = -kPosBig;
                     d_stage = 0.f;
@@ -165,19 +165,37 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 if (!act) continue;
                 const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
 
-                // S[q][k] starts from the row term of the exponent; dP from zero
+                // S[q][k] starts from the row term of the exponent, dP from -D_t (so that the accumulator
+                // ends as dP - D, the factor of dS, without a subtraction per element).  The fragment reads
+                // run kAhead products ahead of the MFMAs, in an explicit one-read-per-MFMA pipeline.
+                constexpr int kAhead = 4;
                 f32x16 s, dp;
                 acc_init_rows(s, sm.nl[buf], 32 * sb, h);
+                acc_init_rows(dp, sm.dvec[buf], 32 * sb, h);
+                if (D != 128) {  // d = 64 runs two waves per SIMD, which hide the reads by themselves
 #pragma unroll
-                for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+                    for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
 #pragma unroll
-                for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
+                    for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
+                } else {
+                    bf16x8 fr[2 * KC];
+                    auto fetch = [&](int f) __attribute__((always_inline)) {
+                        fr[f] = lds_read_frag<D>(f < KC ? qt : gt, 32 * sb, f % KC, lane);
+                    };
 #pragma unroll
-                for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
-                f32x4 dvv[4];
+                    for (int f = 0; f < kAhead; ++f) fetch(f);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 8 + kAhead, 0);
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    dvv[g] = *reinterpret_cast<const f32x4*>(&sm.dvec[buf][32 * sb + 8 * g + 4 * h]);
+                    for (int f = 0; f < 2 * KC; ++f) {
+                        if (f < KC) s = mfma32(fr[f], kf[f], s);
+                        else dp = mfma32(fr[f], vf[f - KC], dp);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (f + kAhead < 2 * KC) {
+                            fetch(f + kAhead);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                    }
+                }
                 float p[16], ds[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
@@ -191,19 +209,42 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    ds[v] = p[v] * (dp[v] - dvv[v >> 2][v & 3]);
+                    ds[v] = p[v] * dp[v];
                     colsum += ds[v];
                 }
                 bf16x8 pf[2], dsf[2];
                 acc_to_bfrag(p, pf);
                 acc_to_bfrag(ds, dsf);
+                if (D != 128) {
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
+                    for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
-                        dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
+                        for (int db = 0; db < DB; ++db) {
+                            dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
+                            dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
+                        }
+                } else {
+                    constexpr int NB = 4 * DB;  // products: (c2, db, dV | dK)
+                    bf16x8 fr[NB];
+                    auto fetch = [&](int f) __attribute__((always_inline)) {
+                        const int c2 = f / (2 * DB), db = (f / 2) % DB;
+                        fr[f] = lds_read_tr_frag<D>((f & 1) ? qt : gt, 32 * sb + 16 * c2, db, lane);
+                    };
+#pragma unroll
+                    for (int f = 0; f < kAhead; ++f) fetch(f);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
+#pragma unroll
+                    for (int f = 0; f < NB; ++f) {
+                        const int c2 = f / (2 * DB), db = (f / 2) % DB;
+                        if (f & 1) dk_acc[db] = mfma32(fr[f], dsf[c2], dk_acc[db]);
+                        else dv_acc[db] = mfma32(fr[f], pf[c2], dv_acc[db]);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (f + kAhead < NB) {
+                            fetch(f + kAhead);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        }
                     }
+                }
             }
             if (i < i_hi) store_vec(buf ^ 1);
             __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
