@@ -321,10 +321,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
             gf[kc] = *reinterpret_cast<const bf16x8*>(dO + roff + 16 * kc);
         }
     }
-    float nlsub = -kPosBig, dt = 0.f;  // lane-constant part of the exponent: -(L_t + c_t - c_base) log2 e
+    float nlsub = -kPosBig, ndt = 0.f;  // lane-constant part of the exponent: -(L_t + c_t - c_base) log2 e
     if (t < N) {
         nlsub = -(L[(size_t)bh * N + t] + (ch[t] - cbase)) * kLog2e;
-        dt = Dv[(size_t)bh * N + t];
+        ndt = -Dv[(size_t)bh * N + t];
     }
 
     f32x16 dq_acc[DB];
@@ -366,15 +366,32 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
             if (!act) continue;
             const bool full = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
 
-            // S^T[k][q] starts from the key term of the exponent; dP^T from zero
+            // S^T[k][q] starts from the key term of the exponent, dP^T from -D_t (lane-constant), so that
+            // the accumulator ends as dP - D.  The fragment reads run kAhead products ahead of the MFMAs.
+            constexpr int kAhead = 4;
             f32x16 s, dp;
             acc_init_rows(s, sm.g[buf], 32 * sb, h);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+            for (int v = 0; v < 16; ++v) dp[v] = ndt;
+            {
+                bf16x8 fr[2 * KC];
+                auto fetch = [&](int f) __attribute__((always_inline)) {
+                    fr[f] = lds_read_frag<D>(f < KC ? kt : vt, 32 * sb, f % KC, lane);
+                };
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(kt, 32 * sb, kc, lane), qf[kc], s);
+                for (int f = 0; f < kAhead; ++f) fetch(f);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4 + kAhead, 0);
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(vt, 32 * sb, kc, lane), gf[kc], dp);
+                for (int f = 0; f < 2 * KC; ++f) {
+                    if (f < KC) s = mfma32(fr[f], qf[f], s);
+                    else dp = mfma32(fr[f], gf[f - KC], dp);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (f + kAhead < 2 * KC) {
+                        fetch(f + kAhead);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                }
+            }
             float ds[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -384,16 +401,30 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
                     const bool keep = (i <= t) && (i > t - w);
                     p = keep ? p : 0.f;
                 }
-                ds[v] = p * (dp[v] - dt);
+                ds[v] = p * dp[v];
                 rowsum += ds[v];
             }
             bf16x8 dsf[2];
             acc_to_bfrag(ds, dsf);
+            {
+                constexpr int NB = 2 * DB;
+                bf16x8 fr[NB];
+                auto fetch = [&](int f) __attribute__((always_inline)) {
+                    fr[f] = lds_read_tr_frag<D>(kt, 32 * sb + 16 * (f / DB), f % DB, lane);
+                };
 #pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2)
+                for (int f = 0; f < kAhead; ++f) fetch(f);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    dq_acc[db] = mfma32(lds_read_tr_frag<D>(kt, 32 * sb + 16 * c2, db, lane), dsf[c2], dq_acc[db]);
+                for (int f = 0; f < NB; ++f) {
+                    dq_acc[f % DB] = mfma32(fr[f], dsf[f / DB], dq_acc[f % DB]);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (f + kAhead < NB) {
+                        fetch(f + kAhead);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    }
+                }
+            }
         }
         if (j < j_hi && tid < kTileRows) sm.g[buf ^ 1][tid] = g_next;
         __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile j+1 has landed
