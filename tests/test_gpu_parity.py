@@ -515,3 +515,45 @@ def test_outputs_do_not_spill_past_their_buffers(g):
     for buf, n in ((Obuf, 333 * 128), (Lbuf, 333)):
         assert (buf[:pad] == 7.0).all() and (buf[pad + n:] == 7.0).all()
     assert not (O == 7.0).all()
+
+
+def test_step_under_graph_capture_replays_bit_exactly(g, oracle):
+    # the whole step (prefix, forward, backward) allocates nothing and clears nothing with memsets, so it
+    # can be captured in a HIP graph; every replay must give the eager run's bits, also with other work
+    # and synchronizations between the replays
+    wl = gi.custom("graph", 1, 4, 3000, 128, 700, "bf16", alpha_mu=-1.0, index=26, backward=True, kv_heads=2)
+    ins = {t: dev(gi.make_tensor(wl, t), "bf16") for t in ("Q", "K", "V", "dO")}
+    alpha = dev(gi.make_tensor(wl, "alpha"), "f32")
+    B, H, N, d = ins["Q"].shape
+    c = torch.empty_like(alpha)
+    O, L = torch.empty_like(ins["Q"]), torch.empty_like(alpha)
+    dQ, dK, dV, dal = torch.empty_like(ins["Q"]), torch.empty_like(ins["K"]), torch.empty_like(ins["V"]), torch.empty_like(alpha)
+    ws = torch.empty(g.gfwa_backward_workspace_bytes(torch.bfloat16, B, H, N, d, wl.w), dtype=torch.uint8, device=DEV)
+
+    def step():
+        g.gfwa_gate_prefix(alpha, c)
+        g.gfwa_forward_gqa(ins["Q"], ins["K"], ins["V"], c, wl.w, wl.scale, O=O, L=L)
+        g.gfwa_backward_gqa(ins["Q"], ins["K"], ins["V"], O, ins["dO"], c, L, wl.w, wl.scale, workspace=ws,
+                            dQ=dQ, dK=dK, dV=dV, dalpha=dal)
+
+    outs = (c, O, L, dQ, dK, dV, dal)
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(float("nan")) if t.is_floating_point() else t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, w_ in zip(outs, want):
+            assert torch.equal(t, w_), f"replay {rep}"
+        step()                                   # eager work between the replays
+        torch.cuda.synchronize()
