@@ -392,16 +392,20 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
                     }
                 }
             }
-            float ds[16];
+            float p[16], ds[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = fast_exp2(fmaf(s[v], sl, nlsub));
-                if (!full) {
+            for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, nlsub));
+            if (!full) {  // one branch per block, not one per element
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
                     const int i = kb0 + acc_row(v, h);
                     const bool keep = (i <= t) && (i > t - w);
-                    p = keep ? p : 0.f;
+                    p[v] = keep ? p[v] : 0.f;
                 }
-                ds[v] = p * dp[v];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                ds[v] = p[v] * dp[v];
                 rowsum += ds[v];
             }
             bf16x8 dsf[2];
