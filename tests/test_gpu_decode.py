@@ -152,3 +152,16 @@ def test_decode_rows_outside_the_window_are_not_read(g, oracle):
     o2, L2 = g.gfwa_decode(dev(q, "f32"), dev(Kp, "f32"), dev(Vp, "f32"), dev(c32, "f32"), dev(pos, "i32"), 100, wl.scale)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2) and torch.equal(L1, L2)
+
+
+def test_decode_clamps_positions_outside_the_cache(g, oracle):
+    # a position below 0 or past the cache is taken as the first / last slot: nothing outside is touched
+    wl, q, Kc, Vc, alpha, _ = make_case(3, 4, 2, 300, 64, 50, "f32", 27)
+    c32 = oracle.gate_prefix(alpha).astype(np.float32)
+    args = (dev(q, "f32"), dev(Kc, "f32"), dev(Vc, "f32"), dev(c32, "f32"))
+    bad = torch.tensor([-5, 300, 1 << 30], dtype=torch.int32, device=DEV)
+    good = torch.tensor([0, 299, 299], dtype=torch.int32, device=DEV)
+    o1, L1 = g.gfwa_decode(*args, bad, 50, wl.scale)
+    o2, L2 = g.gfwa_decode(*args, good, 50, wl.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(L1, L2)
