@@ -272,6 +272,271 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     }
 }
 
+// 8-wave variant (d = 128): two waves per SIMD.  The workgroup still owns 128 keys, but the waves kg
+// and kg + 4, which share a SIMD, both work on key group kg and take one of the two 32-query blocks
+// of every tile each, so that one wave's MFMAs run while the other does its softmax arithmetic or
+// waits for LDS.  Two waves per SIMD leave 256 registers per wave: the dK, dV accumulators (128) and
+// S, dP (32) stay, the K and V fragments do not - the 128 keys of K and V are staged in LDS once per
+// workgroup and read as B operands like the Q and dO tiles are read as A operands.  At the end the
+// two waves of a key group add their accumulators through LDS.
+template <int D>
+struct Dkv8Smem {
+    union {
+        DkvSmem<D> t;
+        float red[4][16 * (D / 32)][64];  // [key group][accumulator register][lane]
+    };
+    TilePairSmem<D> kv;  // a = the two 64-key tiles of K, b = of V
+    float colred[4][32];
+};
+
+template <int D>
+__global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
+    const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
+    float* __restrict__ dc_col, int N, int w, float scale, int num_ktiles, int total_tiles, int H, int G) {
+    constexpr int BK = 128;  // keys per workgroup, 32 per wave
+    constexpr int KC = D / 16, DB = D / 32;
+    __shared__ Dkv8Smem<D> sm8;
+    auto& sm = sm8.t;
+
+    const int tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bkv = tile / num_ktiles;  // flat key/value head; its G query heads are visited in turn
+    const int k0 = (tile % num_ktiles) * BK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = wv & 3;     // 32-key group; waves kg and kg + 4 share it (and a SIMD)
+    const int half = wv >> 2;  // ... and take one 32-query block of every tile each
+    const int h = lane >> 5, lk = lane & 31;
+    const float sl = scale * kLog2e;
+    const float inv_scale = 1.0f / scale;
+
+    const size_t head_off = (size_t)bkv * N * D;
+    const int Hkv = H / G;
+    const int bh0 = (bkv / Hkv) * H + (bkv % Hkv) * G;  // first query head of the group
+
+    const int kw0 = k0 + 32 * kg;  // first key of this wave
+    const int key = kw0 + lk;
+
+    // K^T and V^T fragments (B operands: column = key, k = head dimension) come from the staged tiles
+    const char* ktile = sm8.kv.a[kg >> 1];
+    const char* vtile = sm8.kv.b[kg >> 1];
+    const int krow0 = 32 * (kg & 1);
+
+    f32x16 dk_acc[DB], dv_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            dk_acc[db][v] = 0.f;
+            dv_acc[db][v] = 0.f;
+        }
+
+    // queries that can see a key of this tile: k0 <= t <= min(N-1, k0+BK-1+w-1)
+    const int t_hi = (int)min((long)N - 1, (long)k0 + BK - 1 + (long)w - 1);
+    const int i_lo = k0 / kTileRows, i_hi = t_hi / kTileRows;
+    const int ifull = N / kTileRows;
+
+    TilePairLoader<D, 8> loader;
+    loader.init(wv, lane);
+    {  // K and V of the 128 keys; the wait and barrier in front of the first query tile cover them
+        const char* Kh = reinterpret_cast<const char*>(K + head_off);
+        const char* Vh = reinterpret_cast<const char*>(V + head_off);
+        loader.load(Kh, Vh, k0 / kTileRows, ifull, N, sm8.kv.a[0], sm8.kv.b[0]);
+        loader.load(Kh, Vh, k0 / kTileRows + 1, ifull, N, sm8.kv.a[1], sm8.kv.b[1]);
+    }
+    for (int qh = 0; qh < G; ++qh) {
+        const int bh = bh0 + qh;
+        const size_t qhead_off = (size_t)bh * N * D;
+        const char* Qh = reinterpret_cast<const char*>(Q + qhead_off);
+        const char* Gh = reinterpret_cast<const char*>(dO + qhead_off);
+        const float* ch = c + (size_t)bh * N;
+        const float* Lh = L + (size_t)bh * N;
+        const float* Dh = Dv + (size_t)bh * N;
+        const float cbase = ch[k0];
+        const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
+        float colsum = 0.f;
+        // per-row vectors of query tile i, one row per thread of the first wave
+        float nl_stage = -kPosBig, d_stage = 0.f;
+        auto load_vec = [&](int i) {
+            if (tid < kTileRows) {
+                const int t = i * kTileRows + tid;
+                if (t < N) {
+                    nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
+                    d_stage = -Dh[t];
+                } else {
+                    nl_stage = -kPosBig;
+                    d_stage = 0.f;
+                }
+            }
+        };
+        auto store_vec = [&](int buf) {
+            if (tid < kTileRows) {
+                sm.nl[buf][tid] = nl_stage;
+                sm.dvec[buf][tid] = d_stage;
+            }
+        };
+        loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
+        load_vec(i_lo);
+        store_vec(0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+
+        for (int i = i_lo; i <= i_hi; ++i) {
+            const int buf = (i - i_lo) & 1;
+            if (i < i_hi) {
+                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
+                load_vec(i + 1);
+            }
+            const char* qt = sm.qg.a[buf];
+            const char* gt = sm.qg.b[buf];
+            {
+                const int sb = half;
+                const int qb0 = i * kTileRows + 32 * sb;
+                const bool act = (kw0 <= qb0 + 31) && (kw0 + 31 > qb0 - w) && (kw0 < N) && (qb0 < N);
+                if (act) {
+                const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
+
+                // S[q][k] starts from the row term of the exponent, dP from -D_t (so that the accumulator
+                // ends as dP - D, the factor of dS, without a subtraction per element).  The fragment reads
+                // run kAhead products ahead of the MFMAs, in an explicit one-read-per-MFMA pipeline.
+                constexpr int kAhead = 2;
+                f32x16 s, dp;
+                acc_init_rows(s, sm.nl[buf], 32 * sb, h);
+                acc_init_rows(dp, sm.dvec[buf], 32 * sb, h);
+                if (D != 128) {  // d = 64 runs two waves per SIMD, which hide the reads by themselves
+#pragma unroll
+                    for (int kc = 0; kc < KC; ++kc)
+                        s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), lds_read_frag<D>(ktile, krow0, kc, lane), s);
+#pragma unroll
+                    for (int kc = 0; kc < KC; ++kc)
+                        dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), lds_read_frag<D>(vtile, krow0, kc, lane), dp);
+                } else {
+                    bf16x8 fr[2 * KC], fk[2 * KC];
+                    auto fetch = [&](int f) __attribute__((always_inline)) {
+                        fr[f] = lds_read_frag<D>(f < KC ? qt : gt, 32 * sb, f % KC, lane);
+                        fk[f] = lds_read_frag<D>(f < KC ? ktile : vtile, krow0, f % KC, lane);
+                    };
+#pragma unroll
+                    for (int f = 0; f < kAhead; ++f) fetch(f);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 8 + 2 * kAhead, 0);
+#pragma unroll
+                    for (int f = 0; f < 2 * KC; ++f) {
+                        if (f < KC) s = mfma32(fr[f], fk[f], s);
+                        else dp = mfma32(fr[f], fk[f], dp);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (f + kAhead < 2 * KC) {
+                            fetch(f + kAhead);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        }
+                    }
+                }
+                float p[16], ds[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
+                if (!full) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = qb0 + acc_row(v, h);
+                        const bool keep = (key <= t) && (key > t - w);
+                        p[v] = keep ? p[v] : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    ds[v] = p[v] * dp[v];
+                    colsum += ds[v];
+                }
+                bf16x8 pf[2], dsf[2];
+                acc_to_bfrag(p, pf);
+                acc_to_bfrag(ds, dsf);
+                if (D != 128) {
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                        for (int db = 0; db < DB; ++db) {
+                            dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
+                            dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
+                        }
+                } else {
+                    constexpr int NB = 4 * DB;  // products: (c2, db, dV | dK)
+                    bf16x8 fr[NB];
+                    auto fetch = [&](int f) __attribute__((always_inline)) {
+                        const int c2 = f / (2 * DB), db = (f / 2) % DB;
+                        fr[f] = lds_read_tr_frag<D>((f & 1) ? qt : gt, 32 * sb + 16 * c2, db, lane);
+                    };
+#pragma unroll
+                    for (int f = 0; f < kAhead; ++f) fetch(f);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
+#pragma unroll
+                    for (int f = 0; f < NB; ++f) {
+                        const int c2 = f / (2 * DB), db = (f / 2) % DB;
+                        if (f & 1) dk_acc[db] = mfma32(fr[f], dsf[c2], dk_acc[db]);
+                        else dv_acc[db] = mfma32(fr[f], pf[c2], dv_acc[db]);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (f + kAhead < NB) {
+                            fetch(f + kAhead);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        }
+                    }
+                }
+                }
+            }
+            if (i < i_hi) store_vec(buf ^ 1);
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
+            __syncthreads();
+        }
+
+        // column sums of the two query halves
+        float cs = xhalf_sum(colsum);
+        if (half == 1 && h == 0) sm8.colred[kg][lk] = cs;
+        __syncthreads();
+        if (half == 0 && h == 0) {
+            cs += sm8.colred[kg][lk];
+            if (key < N) dc_col[(size_t)bh * N + key] = cs;
+        }
+    }  // query heads of the group
+
+    // the two waves of a key group add their accumulators through LDS (the tile buffers are free now)
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        __syncthreads();
+        if (half == 1) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sm8.red[kg][16 * db + v][lane] = pass == 0 ? dk_acc[db][v] : dv_acc[db][v];
+        }
+        __syncthreads();
+        if (half == 0) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    if (pass == 0) dk_acc[db][v] += sm8.red[kg][16 * db + v][lane];
+                    else dv_acc[db][v] += sm8.red[kg][16 * db + v][lane];
+                }
+        }
+    }
+    if (half == 1) return;
+
+    if (key < N) {
+        bf16_t* dkrow = dK + head_off + (size_t)key * D;
+        bf16_t* dvrow = dV + head_off + (size_t)key * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 k4 = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale,
+                            dk_acc[db][4 * g + 2] * scale, dk_acc[db][4 * g + 3] * scale};
+                f32x4 v4 = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2],
+                            dv_acc[db][4 * g + 3]};
+                *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(k4, bf16x4);
+                *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(v4, bf16x4);
+            }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // 3. dQ, row sums: query-stationary
 // ------------------------------------------------------------------------------------------
@@ -469,9 +734,14 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     const int nk = (N + 127) / 128;
     {
         ProfScope prof(kKernDkv, s);
-        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(kThreads), 0, s,
-                           (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
-                           (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
+        if (D == 128)  // two waves per SIMD that share a key group (at d = 64 the 4-wave kernel has them already)
+            hipLaunchKernelGGL((bwd_dkv8_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(2 * kThreads), 0, s,
+                               (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                               (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
+        else
+            hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(kThreads), 0, s,
+                               (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                               (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
     }
     const int nq = (N + 127) / 128;
     {
