@@ -2,21 +2,22 @@
 //
 // Four launches, no atomics, deterministic:
 //   1. rowdot:   D_t = <O_t, dO_t>                                   (HBM-bound)
-//   2. dkv:      key-stationary.  A wave keeps 32 keys of K and V in registers as MFMA B operands
-//                and streams 64-query tiles of Q and dO through LDS (direct global->LDS loads):
-//                  S[q][k]   = Q (A, LDS)       x K^T (B, regs)      P  = exp2(x - L)
-//                  dP[q][k]  = dO (A, LDS)      x V^T (B, regs)      dS = P (dP - D)
+//   2. dkv:      key-stationary.  A wave works on 32 keys, whose K and V are MFMA B operands (in
+//                registers at d = 64, staged in LDS at d = 128, see the two kernels), and streams
+//                64-query tiles of Q and dO through LDS (direct global->LDS loads):
+//                  S[q][k]   = Q (A, LDS)       x K^T (B)            P  = exp2(x - L)
+//                  dP[q][k]  = dO (A, LDS)      x V^T (B)  - D       dS = P (dP - D)
 //                  dV^T[dd][k] += dO^T (A, LDS transposing read) x P  (B = accumulator registers)
 //                  dK^T[dd][k] += Q^T  (A, LDS transposing read) x dS (B = accumulator registers)
 //                plus the column sums of dS.  A lane owns one key.
 //   3. dq:       query-stationary, the forward's layout.  A lane owns one query:
-//                  S^T[k][q] = K (A, LDS) x Q^T (B, regs)   dP^T[k][q] = V (A, LDS) x dO^T (B, regs)
+//                  S^T[k][q] = K (A, LDS) x Q^T (B, regs)   dP^T[k][q] = V (A, LDS) x dO^T (B, regs) - D
 //                  dQ^T[dd][q] += K^T (A, LDS transposing read) x dS^T (B = accumulator registers)
 //                plus the row sums of dS.
 //   4. reverse scan of (column sums - row sums) -> dalpha   (gate_scan.hip)
 // In both kernels the row- (dkv) or key- (dq) dependent part of the exponent rides in the MFMA
 // accumulator (it is initialised from an LDS vector before the product), the lane-constant part is
-// the addend of the single fused multiply-add in front of exp2.
+// the addend of the single fused multiply-add in front of exp2; the dP accumulator starts from -D.
 // The row sums are analytically zero but are kept: with D formed from the rounded O they carry
 // exactly the error that would otherwise accumulate over the whole suffix in the reverse scan.
 #include "gfwa_device.h"
