@@ -735,7 +735,7 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     const int nk = (N + 127) / 128;
     {
         ProfScope prof(kKernDkv, s);
-        if (D == 128)  // two waves per SIMD that share a key group (at d = 64 the 4-wave kernel has them already)
+        if constexpr (D == 128)  // two waves per SIMD that share a key group (at d = 64 the 4-wave kernel has them already)
             hipLaunchKernelGGL((bwd_dkv8_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(2 * kThreads), 0, s,
                                (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
                                (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
