@@ -157,7 +157,7 @@ def make_tensor(wl: Workload, tag: str, heads: Optional[np.ndarray] = None) -> n
 
 def make_gate_inputs(wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
     """Inputs of the gate activation, [B,H,N] fp32: the pre-activation h ~ N(alpha_mu, 1) (the same draw
-    that `alpha` is the softplus of) and a positive amplitude beta, log-normal around 1."""
+    that `alpha` is the softplus of) and a positive amplitude beta, log-normal with median 1."""
     shape = (wl.B, wl.H, wl.N)
     h = normal(wl.seed("alpha"), (wl.B * wl.H, wl.N), mean=wl.alpha_mu).reshape(shape).astype(np.float32)
     beta = np.exp(0.5 * normal(wl.seed("alpha") + 1000003, shape)).astype(np.float32)
