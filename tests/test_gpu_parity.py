@@ -557,3 +557,31 @@ def test_step_under_graph_capture_replays_bit_exactly(g, oracle):
             assert torch.equal(t, w_), f"replay {rep}"
         step()                                   # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_offsets_beyond_32_bits(g, oracle):
+    # 2^31 elements per [B,H,N,d] tensor: element offsets of the last heads do not fit 32 bits.  Inputs
+    # are drawn on the GPU (seeded); the oracle gets the first and the last head.
+    B, H, N, d, w = 8, 32, 65536, 128, 64
+    assert B * H * N * d == 1 << 31
+    gen = torch.Generator(device=DEV).manual_seed(31)
+    mk = lambda: torch.randn(B, H, N, d, device=DEV, generator=gen, dtype=torch.bfloat16)
+    Q, K, V, dO = mk(), mk(), mk(), mk()
+    alpha = torch.nn.functional.softplus(torch.randn(B, H, N, device=DEV, generator=gen) - 1.0)
+    scale = 1.0 / d ** 0.5
+    c = g.gfwa_gate_prefix(alpha)
+    O, L = g.gfwa_forward(Q, K, V, c, w, scale)
+    dQ, dK, dV, dalpha = g.gfwa_backward(Q, K, V, O, dO, c, L, w, scale)
+    torch.cuda.synchronize()
+    for b, h in ((0, 0), (B - 1, H - 1)):
+        note("  head", b, h)
+        pick = lambda t: host(t[b, h])[None, None]
+        c_ref = oracle.gate_prefix(pick(alpha))
+        assert np.abs(pick(c) - c_ref).max() <= 4 * np.finfo(np.float32).eps * c_ref.max()
+        c32 = pick(c)
+        O_ref, L_ref = oracle.forward_from_c(pick(Q), pick(K), pick(V), c32, w, scale)
+        LAST["c_span"] = float(c32.max())
+        check_bf16_forward(pick(O), pick(L), O_ref, L_ref, tag="big")
+        ref = oracle.backward_from_c(pick(Q), pick(K), pick(V), c32, pick(dO), w, scale)
+        got = {"dQ": pick(dQ), "dK": pick(dK), "dV": pick(dV), "dalpha": pick(dalpha)}
+        check_grads(got, ref, 1e-2, "big")
