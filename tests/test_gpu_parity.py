@@ -585,3 +585,32 @@ def test_offsets_beyond_32_bits(g, oracle):
         ref = oracle.backward_from_c(pick(Q), pick(K), pick(V), c32, pick(dO), w, scale)
         got = {"dQ": pick(dQ), "dK": pick(dK), "dV": pick(dV), "dalpha": pick(dalpha)}
         check_grads(got, ref, 1e-2, "big")
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 1, 2, 3, 4]))
+        Hkv = int(rng.integers(1, 3))
+        N = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 1400)]))
+        w = int(rng.choice([1, rng.integers(2, 70), rng.integers(70, 600), N, N + 17, 4 * N + 1]))
+        out.append((int(rng.integers(1, 3)), Hkv * G, Hkv, N, d, max(1, w)))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_random_shapes_forward_backward(g, oracle, dtype):
+    # seeded random shapes: ragged N, windows shorter and longer than the sequence, grouped heads
+    for case, (B, H, Hkv, N, d, w) in enumerate(_random_shapes(28, 2512)):
+        note("random shape", case, (B, H, Hkv, N, d, w), dtype)
+        wl = gi.custom("rnd", B, H, N, d, w, dtype, alpha_mu=-1.0, index=28 + case % 4, backward=True, kv_heads=Hkv)
+        got, ref = run_gqa(g, oracle, wl)
+        if dtype == "bf16":
+            check_bf16_forward(got["O"], got["L"], ref["O"], ref["L"], tag=f"rnd{case}")
+            check_grads(got, ref, 1e-2, f"rnd{case}")
+        else:
+            assert rel_inf(got["O"], ref["O"]) <= 1e-5
+            assert (np.abs(got["L"] - ref["L"]) <= 1e-5 * np.abs(ref["L"]).max() + 1e-5).all()
+            check_grads(got, ref, 1e-5, f"rnd{case}")
