@@ -169,16 +169,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 // S[q][k] starts from the row term of the exponent, dP from -D_t (so that the accumulator
                 // ends as dP - D, the factor of dS, without a subtraction per element).  The fragment reads
                 // run kAhead products ahead of the MFMAs, in an explicit one-read-per-MFMA pipeline.
-                constexpr int kAhead = 4;
+                constexpr int kAhead = D == 128 ? 4 : 2;  // what the register budget of two waves per SIMD allows
                 f32x16 s, dp;
                 acc_init_rows(s, sm.nl[buf], 32 * sb, h);
                 acc_init_rows(dp, sm.dvec[buf], 32 * sb, h);
-                if (D != 128) {  // d = 64 runs two waves per SIMD, which hide the reads by themselves
-#pragma unroll
-                    for (int kc = 0; kc < KC; ++kc) s = mfma32(lds_read_frag<D>(qt, 32 * sb, kc, lane), kf[kc], s);
-#pragma unroll
-                    for (int kc = 0; kc < KC; ++kc) dp = mfma32(lds_read_frag<D>(gt, 32 * sb, kc, lane), vf[kc], dp);
-                } else {
+                {
                     bf16x8 fr[2 * KC];
                     auto fetch = [&](int f) __attribute__((always_inline)) {
                         fr[f] = lds_read_frag<D>(f < KC ? qt : gt, 32 * sb, f % KC, lane);
@@ -216,15 +211,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
                 bf16x8 pf[2], dsf[2];
                 acc_to_bfrag(p, pf);
                 acc_to_bfrag(ds, dsf);
-                if (D != 128) {
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                        for (int db = 0; db < DB; ++db) {
-                            dv_acc[db] = mfma32(lds_read_tr_frag<D>(gt, 32 * sb + 16 * c2, db, lane), pf[c2], dv_acc[db]);
-                            dk_acc[db] = mfma32(lds_read_tr_frag<D>(qt, 32 * sb + 16 * c2, db, lane), dsf[c2], dk_acc[db]);
-                        }
-                } else {
+                {
                     constexpr int NB = 4 * DB;  // products: (c2, db, dV | dK)
                     bf16x8 fr[NB];
                     auto fetch = [&](int f) __attribute__((always_inline)) {
