@@ -92,7 +92,7 @@ def decode_only(args, g, torch) -> int:
     g.gfwa_profile_enable(False)
     prof = {k: v for k, v in g.gfwa_profile_read().items() if v[1]}
     part_ms = prof["decode_partial"][0] / prof["decode_partial"][1]
-    comb_ms = prof["decode_combine"][0] / prof["decode_combine"][1]
+    comb_ms = prof["decode_combine"][0] / prof["decode_combine"][1] if "decode_combine" in prof else 0.0
     gbs = algo / part_ms / 1e6
     print(json.dumps({
         "metric": "GatedFWA decoding step, algorithmic GB/s of the cache-reading kernel", "value": round(gbs, 1),

@@ -10,7 +10,7 @@
 //     workgroup), so the cache is read once per group, not once per head;
 //   * the window is split into chunks (256 keys, longer when the batch alone fills the chip), one
 //     workgroup each; the (reference exponent, sum, output) partials are merged across the four waves
-//     through LDS and across chunks by a second small kernel.
+//     through LDS and, when the window has more than one chunk, across chunks by a second small kernel.
 // With `alpha_t` given the kernel also advances the gate prefix, c[pos] = c[pos-1] + alpha_t, the one
 // step of the scan a decoding step needs.
 #include "gfwa_device.h"
@@ -110,8 +110,8 @@ __device__ __forceinline__ float row_sum(float x) {
 template <typename T, int D, int GT>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ Kc, const T* __restrict__ Vc, float* __restrict__ c,
-    const float* __restrict__ alpha_t, const int* __restrict__ pos, float* __restrict__ part, int H, int G,
-    int Tlen, int w, float scale, int S, int chunk) {
+    const float* __restrict__ alpha_t, const int* __restrict__ pos, float* __restrict__ part,
+    T* __restrict__ o, float* __restrict__ L, int H, int G, int Tlen, int w, float scale, int S, int chunk) {
     constexpr int LPR = D / 8;     // lanes per cache row
     constexpr int RPI = 64 / LPR;  // rows per wave instruction
     constexpr int UN = 4;          // rows per lane group and step
@@ -303,11 +303,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
             ll = fmaf(sm_l[k][g], f, ll);
             oo = fmaf(sm_acc[k][g][col], f, oo);
         }
-        float* rec = part + ((size_t)(bh0 + g) * S + s) * dec_record(D);
-        rec[col] = oo;
-        if (col == 0) {
-            rec[D] = mm;
-            rec[D + 1] = ll;
+        if (S == 1) {  // the whole window in one chunk: this is the result, no merge kernel follows
+            o[(size_t)(bh0 + g) * D + col] = (T)(oo / ll);
+            if (L != nullptr && col == 0) L[bh0 + g] = (mm + log2f(ll)) * kLn2;
+        } else {
+            float* rec = part + ((size_t)(bh0 + g) * S + s) * dec_record(D);
+            rec[col] = oo;
+            if (col == 0) {
+                rec[D] = mm;
+                rec[D + 1] = ll;
+            }
         }
     }
 }
@@ -360,15 +365,15 @@ static hipError_t launch_decode(const T* q, const T* Kc, const T* Vc, float* c, 
         ProfScope prof(kKernDecode, s);
         if (GT == 4)
             hipLaunchKernelGGL((decode_partial_kernel<T, D, 4>), dim3(grid), dim3(kDecThreads), 0, s, q, Kc, Vc, c,
-                               alpha_t, pos, part, H, G, Tlen, w, scale, S, chunk);
+                               alpha_t, pos, part, o, L, H, G, Tlen, w, scale, S, chunk);
         else if (GT == 2)
             hipLaunchKernelGGL((decode_partial_kernel<T, D, 2>), dim3(grid), dim3(kDecThreads), 0, s, q, Kc, Vc, c,
-                               alpha_t, pos, part, H, G, Tlen, w, scale, S, chunk);
+                               alpha_t, pos, part, o, L, H, G, Tlen, w, scale, S, chunk);
         else
             hipLaunchKernelGGL((decode_partial_kernel<T, D, 1>), dim3(grid), dim3(kDecThreads), 0, s, q, Kc, Vc, c,
-                               alpha_t, pos, part, H, G, Tlen, w, scale, S, chunk);
+                               alpha_t, pos, part, o, L, H, G, Tlen, w, scale, S, chunk);
     }
-    {
+    if (S > 1) {
         ProfScope prof(kKernDecodeCombine, s);
         hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(B * H), dim3(D), 0, s, part, o, L, S);
     }
