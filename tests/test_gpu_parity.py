@@ -614,3 +614,32 @@ def test_random_shapes_forward_backward(g, oracle, dtype):
             assert rel_inf(got["O"], ref["O"]) <= 1e-5
             assert (np.abs(got["L"] - ref["L"]) <= 1e-5 * np.abs(ref["L"]).max() + 1e-5).all()
             check_grads(got, ref, 1e-5, f"rnd{case}")
+
+
+def test_gate_kernels_with_pointers_off_the_16_byte_grid(g, oracle):
+    # 4-byte aligned but not 16-byte aligned buffers take the element-wise path of the scan kernels
+    B, H, N = 2, 3, 1000
+    wl = gi.custom("unal", B, H, N, 64, 8, alpha_mu=-1.0, index=5)
+    h, beta = gi.make_gate_inputs(wl)
+    dal = gi.normal(wl.seed("dO"), h.shape).astype(np.float32)
+    n = B * H * N
+
+    def shifted(x):  # same values, storage starting 4 bytes into an allocation
+        buf = torch.empty(n + 1, dtype=torch.float32, device=DEV)
+        view = buf[1:].view(B, H, N)
+        view.copy_(torch.from_numpy(x).to(DEV))
+        assert view.data_ptr() % 16 == 4
+        return view
+
+    hs, bs, ds = shifted(h), shifted(beta), shifted(dal)
+    out = shifted(np.zeros_like(h))
+    c = host(g.gfwa_gate_activation_prefix(hs, bs, GATE_EPS, c=out))
+    ref = oracle.gate_prefix(oracle.gate_activation(h, beta, GATE_EPS))
+    assert np.abs(c - ref).max() <= 8 * np.finfo(np.float32).eps * ref.max()
+    c2 = host(g.gfwa_gate_prefix(hs, c=out))
+    ref2 = oracle.gate_prefix(h)
+    assert np.abs(c2 - ref2).max() <= 4 * np.finfo(np.float32).eps * np.abs(ref2).max() + 1e-6
+    dh_o, db_o = shifted(np.zeros_like(h)), shifted(np.zeros_like(h))
+    dh, dbeta = g.gfwa_gate_activation_backward(hs, bs, GATE_EPS, ds, dh=dh_o, dbeta=db_o)
+    rh, rb = oracle.gate_activation_backward(h, beta, GATE_EPS, dal)
+    assert rel_l2(host(dh), rh) <= 1e-6 and rel_l2(host(dbeta), rb) <= 1e-6
