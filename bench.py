@@ -25,17 +25,21 @@ PEAK_HBM_GBS = 8000.0
 
 
 def gate_only(args, g, torch) -> int:
-    """The memory-bound gate kernels alone, at a size that saturates HBM; algorithmic bytes as in main()."""
+    """The memory-bound gate kernels alone, at a size that saturates HBM; algorithmic bytes as in main()
+    (the scan-then-propagate variants read their inputs twice: 12 and 20 bytes per element)."""
     B, H, N = (int(x) for x in args.gate_only.split(","))
     gen = torch.Generator(device="cuda:0").manual_seed(1)
     hpre = torch.randn(B, H, N, device="cuda:0", generator=gen) - 1.0
     beta = torch.exp(0.5 * torch.randn(B, H, N, device="cuda:0", generator=gen))
     out1, out2, out3 = torch.empty_like(hpre), torch.empty_like(hpre), torch.empty_like(hpre)
+    ws = torch.empty(g.gfwa_gate_scan_workspace_bytes(B, H, N), dtype=torch.uint8, device="cuda:0")
     calls = {
         "gate_prefix_scan": (8.0, lambda: g.gfwa_gate_prefix(hpre, out1)),
         "gate_activation_prefix_scan": (12.0, lambda: g.gfwa_gate_activation_prefix(hpre, beta, args.gate_eps, out1)),
         "gate_activation_bwd": (20.0, lambda: g.gfwa_gate_activation_backward(hpre, beta, args.gate_eps, out1,
                                                                                out2, out3)),
+        "gate_prefix_stp": (12.0, lambda: g.gfwa_gate_prefix_stp(hpre, c=out1, workspace=ws)),
+        "gate_activation_prefix_stp": (20.0, lambda: g.gfwa_gate_prefix_stp(hpre, beta, args.gate_eps, c=out1, workspace=ws)),
         "plain_copy": (8.0, lambda: out2.copy_(hpre)),
     }
     res = {}

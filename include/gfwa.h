@@ -67,6 +67,19 @@ int gfwa_gate_activation_prefix(const float *hpre, const float *beta, float eps,
                                 int N, gfwa_stream_t stream);
 
 /*
+ * The same prefix by scan-then-propagate (paper App. "Preprocessing via Scan-Then-Propagate"): every row
+ * is cut into segments, one launch sums the segments (recomputing the activation), a second one scans
+ * each segment starting from the fp64 sum of the segments before it.  It reads the inputs twice and is
+ * meant for few, very long rows, where one workgroup per row leaves the chip idle.
+ * in: [B,H,N] fp32 - alpha when beta is NULL (eps ignored), else the pre-activation h with beta [B,H,N]
+ * as in gfwa_gate_activation_prefix.  c: [B,H,N] fp32 out.  workspace: device scratch of at least
+ * gfwa_gate_scan_workspace_bytes(B, H, N) bytes, 8-byte aligned, contents undefined before and after.
+ */
+size_t gfwa_gate_scan_workspace_bytes(int B, int H, int N);
+int gfwa_gate_prefix_stp(const float *in, const float *beta, float eps, float *c, void *workspace,
+                         size_t workspace_bytes, int B, int H, int N, gfwa_stream_t stream);
+
+/*
  * Its derivative (chain rule on the definition in Sec. 3.2; the paper prints no listing for it):
  * from d(alpha) as gfwa_backward returns it,
  *
@@ -168,11 +181,12 @@ int gfwa_version(void);
  * Instrumentation (not part of the method): per-kernel timing with HIP events recorded on the
  * caller's stream around every kernel the library launches.  gfwa_profile_enable(1) clears the
  * records and starts recording (at most 8192 launches are kept), gfwa_profile_enable(0) stops.
- * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 10), the
- * summed duration in milliseconds and the number of launches; n must be >= 10.  Kernel ids:
+ * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 12), the
+ * summed duration in milliseconds and the number of launches; n must be >= 12.  Kernel ids:
  * 0 gate prefix scan, 1 forward, 2 backward row-dot (D), 3 backward dK/dV, 4 backward dQ,
  * 5 gate-gradient reverse scan, 6 gate activation + prefix scan, 7 gate activation backward,
- * 8 decoding step (per-chunk partials), 9 decoding step (merge of the chunks);
+ * 8 decoding step (per-chunk partials), 9 decoding step (merge of the chunks), 10 and 11 the two
+ * launches of gfwa_gate_prefix_stp (segment sums, scan of the segments);
  * gfwa_profile_kernel_name gives the same as text.
  * Not thread-safe; host memory only.
  */

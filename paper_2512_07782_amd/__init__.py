@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     gfwa_gate_activation_backward,
     gfwa_gate_activation_prefix,
     gfwa_gate_prefix,
+    gfwa_gate_prefix_stp,
+    gfwa_gate_scan_workspace_bytes,
     gfwa_profile_enable,
     gfwa_profile_kernel_name,
     gfwa_profile_read,

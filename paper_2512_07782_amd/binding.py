@@ -19,10 +19,10 @@ _lib: Optional[ctypes.CDLL] = None
 GFWA_BF16, GFWA_F32 = 0, 1
 
 EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
-           "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode",
+           "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes", "gfwa_gate_prefix_stp",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
-N_KERNELS = 10
+N_KERNELS = 12
 
 
 class GfwaError(RuntimeError):
@@ -67,6 +67,10 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_decode.argtypes = [i, vp, vp, vp, fp, fp, vp, vp, fp, vp, ctypes.c_size_t, i, i, i, i, i, i, f, vp]
     lib.gfwa_decode.restype = i
+    lib.gfwa_gate_scan_workspace_bytes.argtypes = [i, i, i]
+    lib.gfwa_gate_scan_workspace_bytes.restype = ctypes.c_size_t
+    lib.gfwa_gate_prefix_stp.argtypes = [fp, fp, f, fp, vp, ctypes.c_size_t, i, i, i, vp]
+    lib.gfwa_gate_prefix_stp.restype = i
     lib.gfwa_strerror.argtypes = [i]
     lib.gfwa_strerror.restype = ctypes.c_char_p
     lib.gfwa_version.argtypes = []
@@ -164,6 +168,34 @@ def gfwa_gate_activation_backward(hpre: torch.Tensor, beta: torch.Tensor, eps: f
                                                         dalpha.data_ptr(), dh.data_ptr(), dbeta.data_ptr(),
                                                         B, H, N, _stream()))
     return dh, dbeta
+
+
+def gfwa_gate_scan_workspace_bytes(B: int, H: int, N: int) -> int:
+    return int(load_library().gfwa_gate_scan_workspace_bytes(B, H, N))
+
+
+def gfwa_gate_prefix_stp(x: torch.Tensor, beta: Optional[torch.Tensor] = None, eps: float = 0.0,
+                         c: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The prefix by scan-then-propagate (for few, very long rows): of x itself when beta is None, else of
+    softplus(beta * x) / (beta + eps).  x, beta, c: [B,H,N] fp32 on the GPU."""
+    if x.dim() != 3:
+        raise ValueError("x must be [B,H,N]")
+    B, H, N = x.shape
+    _need(x, (B, H, N), torch.float32, "x")
+    if beta is not None:
+        _need(beta, (B, H, N), torch.float32, "beta")
+    if c is None:
+        c = torch.empty_like(x)
+    _need(c, (B, H, N), torch.float32, "c")
+    need = gfwa_gate_scan_workspace_bytes(B, H, N)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _check(load_library().gfwa_gate_prefix_stp(x.data_ptr(), beta.data_ptr() if beta is not None else None,
+                                               float(eps), c.data_ptr(), workspace.data_ptr(),
+                                               workspace.numel() * workspace.element_size(), B, H, N, _stream()))
+    return c
 
 
 def gfwa_forward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, c: torch.Tensor, w: int,

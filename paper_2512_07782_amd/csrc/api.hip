@@ -82,6 +82,22 @@ int gfwa_gate_activation_prefix(const float* hpre, const float* beta, float eps,
     return hip_status(gate_activation_prefix(hpre, beta, eps, c, B * H, N, stream));
 }
 
+size_t gfwa_gate_scan_workspace_bytes(int B, int H, int N) {
+    if (check_dims(B, H, N, 0, 1, false) != GFWA_OK) return 0;
+    return (gate_scan_workspace_bytes(B * H, N) + 255) & ~(size_t)255;
+}
+
+int gfwa_gate_prefix_stp(const float* in, const float* beta, float eps, float* c, void* workspace,
+                         size_t workspace_bytes, int B, int H, int N, gfwa_stream_t stream) {
+    if (!in || !c) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, N, 0, 1, false)) return r;
+    if (beta && !(eps >= 0.0f)) return GFWA_ERR_DIM;
+    if (!aligned(in, 4) || !aligned(c, 4) || (beta && !aligned(beta, 4))) return GFWA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < gfwa_gate_scan_workspace_bytes(B, H, N)) return GFWA_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return GFWA_ERR_ALIGN;
+    return hip_status(gate_prefix_stp(in, beta, eps, c, (double*)workspace, B * H, N, stream));
+}
+
 int gfwa_gate_activation_backward(const float* hpre, const float* beta, float eps, const float* dalpha, float* dh,
                                   float* dbeta, int B, int H, int N, gfwa_stream_t stream) {
     if (!hpre || !beta || !dalpha || !dh || !dbeta) return GFWA_ERR_NULL;
@@ -215,7 +231,7 @@ int gfwa_profile_read(float* total_ms, int* launches, int n) {
 const char* gfwa_profile_kernel_name(int k) {
     static const char* names[kKernCount] = {"gate_prefix_scan", "forward", "bwd_rowdot", "bwd_dkv", "bwd_dq",
                                             "gate_grad_scan", "gate_activation_prefix_scan",
-                                            "gate_activation_bwd", "decode_partial", "decode_combine"};
+                                            "gate_activation_bwd", "decode_partial", "decode_combine", "scan_segment_sum", "scan_propagate"};
     return (k >= 0 && k < kKernCount) ? names[k] : "";
 }
 

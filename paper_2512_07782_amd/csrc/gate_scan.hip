@@ -20,6 +20,7 @@ namespace gfwa {
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
 constexpr int kScanChunk = kScanThreads * 4;
+constexpr int kScanTargetWorkgroups = 2048;  // scan-then-propagate: segments are cut until about this many exist
 
 // Softplus of z in the overflow-safe form of Alg. 1, nu + log(exp(z - nu) + exp(-nu)) with nu = max(z, 0).
 // One of the two exponentials is exp(0) = 1 and the other is e = exp(-|z|), so the logarithm is
@@ -56,13 +57,21 @@ enum ScanInput { kScanPlain = 0, kScanDiff = 1, kScanGate = 2 };
 
 // Logical position p of the scan maps to memory index p (forward) or N-1-p (reverse).
 // MODE kScanDiff: the scanned value is a[idx] - b[idx]; kScanGate: gate_alpha(a[idx], b[idx], eps).
+// With `partial` given (scan-then-propagate, forward scans only) a workgroup takes segment blockIdx.x % P
+// of row blockIdx.x / P, seg_len elements long, and starts from the sum of the row's earlier segments.
 template <bool REVERSE, int MODE>
 __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __restrict__ a,
                                                                  const float* __restrict__ b,
-                                                                 float* __restrict__ out, int N, float eps) {
+                                                                 float* __restrict__ out, int N, float eps,
+                                                                 const double* __restrict__ partial = nullptr,
+                                                                 int seg_len = 0, int P = 1) {
     constexpr bool DIFF = MODE != kScanPlain;  // a second input row
     __shared__ float wave_tot[kScanWaves];
-    const size_t row = (size_t)blockIdx.x * N;
+    __shared__ double wave_carry[kScanWaves];
+    const int seg = partial != nullptr ? (int)(blockIdx.x % P) : 0;
+    const size_t row = (size_t)(partial != nullptr ? blockIdx.x / P : blockIdx.x) * N;
+    const int begin = partial != nullptr ? seg * seg_len : 0;
+    const int end = partial != nullptr ? min(N, begin + seg_len) : N;
     const float* ar = a + row;
     const float* br = DIFF ? b + row : nullptr;
     float* outr = out + row;
@@ -72,10 +81,21 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
     const bool vec = (N % 4 == 0) && ((bits & 15) == 0);
 
     double carry = 0.0;
-    for (int base = 0; base < N; base += kScanChunk) {
+    if (partial != nullptr && seg > 0) {  // sum of the earlier segments of this row, fp64
+        const double* pr = partial + (size_t)(blockIdx.x / P) * P;
+        double acc = 0.0;
+        for (int q = tid; q < seg; q += kScanThreads) acc += pr[q];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0) wave_carry[wv] = acc;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kScanWaves; ++k) carry += wave_carry[k];
+    }
+    for (int base = begin; base < end; base += kScanChunk) {
         const int p0 = base + 4 * tid;
         float v[4] = {0.f, 0.f, 0.f, 0.f};
-        if (vec && p0 + 3 < N) {
+        if (vec && p0 + 3 < end) {
             const int idx = REVERSE ? N - 4 - p0 : p0;
             float4 x = *reinterpret_cast<const float4*>(ar + idx);
             if (MODE == kScanDiff) {
@@ -92,7 +112,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int p = p0 + e;
-                if (p < N) {
+                if (p < end) {
                     const int idx = REVERSE ? N - 1 - p : p;
                     v[e] = MODE == kScanDiff ? ar[idx] - br[idx]
                          : MODE == kScanGate ? gate_alpha(ar[idx], br[idx], eps) : ar[idx];
@@ -125,7 +145,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
         float r[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) r[e] = (float)(excl + (double)v[e]);
-        if (vec && p0 + 3 < N) {
+        if (vec && p0 + 3 < end) {
             const int idx = REVERSE ? N - 4 - p0 : p0;
             const float4 y = REVERSE ? make_float4(r[3], r[2], r[1], r[0]) : make_float4(r[0], r[1], r[2], r[3]);
             *reinterpret_cast<float4*>(outr + idx) = y;
@@ -133,9 +153,59 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int p = p0 + e;
-                if (p < N) outr[REVERSE ? N - 1 - p : p] = r[e];
+                if (p < end) outr[REVERSE ? N - 1 - p : p] = r[e];
             }
         }
+    }
+}
+
+// Phase 1 of scan-then-propagate (App. "Preprocessing via Scan-Then-Propagate"): the sum of every
+// segment, the activation recomputed on the fly when the input is (h, beta).  fp32 per thread over
+// its few elements, fp64 across the workgroup.
+template <int MODE>
+__global__ __launch_bounds__(kScanThreads) void segment_sum_kernel(const float* __restrict__ a,
+                                                                   const float* __restrict__ b,
+                                                                   double* __restrict__ partial, int N, float eps,
+                                                                   int seg_len, int P) {
+    static_assert(MODE == kScanPlain || MODE == kScanGate, "forward scans only");
+    __shared__ double wave_sum[kScanWaves];
+    const int seg = (int)(blockIdx.x % P);
+    const size_t row = (size_t)(blockIdx.x / P) * N;
+    const int begin = seg * seg_len, end = min(N, begin + seg_len);
+    const float* ar = a + row;
+    const float* br = MODE == kScanGate ? b + row : nullptr;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uintptr_t bits = (uintptr_t)a | (MODE == kScanGate ? (uintptr_t)b : (uintptr_t)0);
+    const bool vec = (N % 4 == 0) && ((bits & 15) == 0);
+    float acc = 0.f;
+    for (int base = begin; base < end; base += kScanChunk) {
+        const int p0 = base + 4 * tid;
+        if (vec && p0 + 3 < end) {
+            float4 x = *reinterpret_cast<const float4*>(ar + p0);
+            if (MODE == kScanGate) {
+                const float4 y = *reinterpret_cast<const float4*>(br + p0);
+                x.x = gate_alpha(x.x, y.x, eps); x.y = gate_alpha(x.y, y.y, eps);
+                x.z = gate_alpha(x.z, y.z, eps); x.w = gate_alpha(x.w, y.w, eps);
+            }
+            acc += (x.x + x.y) + (x.z + x.w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int p = p0 + e;
+                if (p < end) acc += MODE == kScanGate ? gate_alpha(ar[p], br[p], eps) : ar[p];
+            }
+        }
+    }
+    double t = (double)acc;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) t += __shfl_xor(t, d, 64);
+    if (lane == 0) wave_sum[wv] = t;
+    __syncthreads();
+    if (tid == 0) {
+        double all = 0.0;
+#pragma unroll
+        for (int k = 0; k < kScanWaves; ++k) all += wave_sum[k];
+        partial[blockIdx.x] = all;
     }
 }
 
@@ -151,6 +221,45 @@ hipError_t gate_activation_prefix(const float* hpre, const float* beta, float ep
     ProfScope prof(kKernGateActPrefix, s);
     hipLaunchKernelGGL((scan_rows_kernel<false, kScanGate>), dim3(rows), dim3(kScanThreads), 0, s, hpre, beta, c,
                        N, eps);
+    return hipGetLastError();
+}
+
+// Scan-then-propagate for few, very long rows: P segments per row, each a workgroup of its own.
+int scan_segments(int rows, int N, int* seg_len) {
+    const int chunks = (N + kScanChunk - 1) / kScanChunk;
+    int P = (kScanTargetWorkgroups + rows - 1) / rows;
+    if (P > chunks) P = chunks;
+    if (P < 1) P = 1;
+    const int seg_chunks = (chunks + P - 1) / P;
+    *seg_len = seg_chunks * kScanChunk;
+    return (chunks + seg_chunks - 1) / seg_chunks;
+}
+
+size_t gate_scan_workspace_bytes(int rows, int N) {
+    return (size_t)rows * ((N + kScanChunk - 1) / kScanChunk) * sizeof(double);  // at most one segment per chunk
+}
+
+hipError_t gate_prefix_stp(const float* in, const float* beta, float eps, float* c, double* partial, int rows,
+                           int N, hipStream_t s) {
+    int seg_len = 0;
+    const int P = scan_segments(rows, N, &seg_len);
+    const dim3 grid((unsigned)(rows * P)), block(kScanThreads);
+    {
+        ProfScope prof(kKernScanSegmentSum, s);
+        if (beta != nullptr)
+            hipLaunchKernelGGL((segment_sum_kernel<kScanGate>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
+        else
+            hipLaunchKernelGGL((segment_sum_kernel<kScanPlain>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
+    }
+    {
+        ProfScope prof(kKernScanPropagate, s);
+        if (beta != nullptr)
+            hipLaunchKernelGGL((scan_rows_kernel<false, kScanGate>), grid, block, 0, s, in, beta, c, N, eps,
+                               (const double*)partial, seg_len, P);
+        else
+            hipLaunchKernelGGL((scan_rows_kernel<false, kScanPlain>), grid, block, 0, s, in, beta, c, N, eps,
+                               (const double*)partial, seg_len, P);
+    }
     return hipGetLastError();
 }
 

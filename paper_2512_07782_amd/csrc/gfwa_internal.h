@@ -11,6 +11,11 @@ hipError_t gate_activation_prefix(const float* hpre, const float* beta, float ep
                                   hipStream_t s);
 hipError_t gate_activation_backward(const float* hpre, const float* beta, float eps, const float* dalpha,
                                     float* dh, float* dbeta, size_t n, hipStream_t s);
+// The same prefix (beta == nullptr: of `in` itself; else of the gate activation of (in, beta)) in two
+// launches that cut every row into segments (scan-then-propagate); partial: gate_scan_workspace_bytes().
+size_t gate_scan_workspace_bytes(int rows, int N);
+hipError_t gate_prefix_stp(const float* in, const float* beta, float eps, float* c, double* partial, int rows,
+                           int N, hipStream_t s);
 // dalpha = reverse inclusive prefix sum of (col - row) along N.
 hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
                           hipStream_t s);
@@ -39,7 +44,8 @@ hipError_t decode(bool bf16, const void* q, const void* Kc, const void* Vc, floa
 
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
 enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,
-                kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernCount };
+                kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernScanSegmentSum,
+                kKernScanPropagate, kKernCount };
 
 // RAII pair of HIP events around one kernel launch on stream s; a no-op unless profiling is on.
 struct ProfScope {

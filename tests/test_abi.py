@@ -24,7 +24,8 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
-                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes",
+                            "gfwa_gate_prefix_stp",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
     for n in names:
@@ -67,6 +68,12 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_forward_gqa(0, good, good, good, good, good, good, 1, 6, 0, 64, 128, 16, f, None) == -2
     assert lib.gfwa_backward_gqa(0, good, good, good, good, good, good, good, good, good, good, good, good,
                                  1 << 20, 1, 6, 5, 64, 128, 16, f, None) == -2
+    # scan-then-propagate
+    assert lib.gfwa_gate_prefix_stp(None, None, f, good, good, 1 << 20, 1, 1, 8, None) == -1
+    assert lib.gfwa_gate_prefix_stp(good, None, f, good, None, 1 << 20, 1, 1, 8, None) == -5
+    assert lib.gfwa_gate_prefix_stp(good, None, f, good, good, 0, 1, 1, 8, None) == -5
+    assert lib.gfwa_gate_prefix_stp(good, good, ctypes.c_float(-1.0), good, good, 1 << 20, 1, 1, 8, None) == -2
+    assert lib.gfwa_gate_scan_workspace_bytes(2, 3, 10000) == 256   # 6 rows x 3 chunks x 8 bytes, padded
     # decoding step
     dec = lambda **kw: [0, kw.get("q", good), good, good, good, None, kw.get("pos", good), good, None,
                         kw.get("ws", good), kw.get("wsb", 1 << 20), 1, kw.get("H", 4), kw.get("Hkv", 2), 64,

@@ -94,6 +94,28 @@ def test_gate_activation_prefix(g, oracle, B, H, N):
     assert np.abs(c - c2).max() <= 8 * np.finfo(np.float32).eps * ref.max()
 
 
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (2, 3, 37), (1, 2, 4096), (2, 2, 4099), (1, 1, 20487), (1, 2, 1000003),
+                                   (4, 16, 16384), (1, 8, 262144)])
+@pytest.mark.parametrize("act", [False, True])
+def test_gate_prefix_scan_then_propagate(g, oracle, B, H, N, act):
+    # the two-launch variant that cuts rows into segments: same definition, same bar as the one-pass scan
+    note("gate_prefix_stp", B, H, N, "activation" if act else "plain")
+    wl = gi.custom("stp", B, H, N, 64, 8, alpha_mu=-1.0, index=6)
+    if act:
+        h, beta = gi.make_gate_inputs(wl)
+        c = host(g.gfwa_gate_prefix_stp(dev(h, "f32"), dev(beta, "f32"), GATE_EPS))
+        ref = oracle.gate_prefix(oracle.gate_activation(h, beta, GATE_EPS))
+        one_pass = host(g.gfwa_gate_activation_prefix(dev(h, "f32"), dev(beta, "f32"), GATE_EPS))
+    else:
+        alpha = gi.make_tensor(wl, "alpha")
+        c = host(g.gfwa_gate_prefix_stp(dev(alpha, "f32")))
+        ref = oracle.gate_prefix(alpha)
+        one_pass = host(g.gfwa_gate_prefix(dev(alpha, "f32")))
+    tol = 8 * np.finfo(np.float32).eps * ref.max()
+    assert np.abs(c - ref).max() <= tol
+    assert np.abs(c - one_pass).max() <= tol
+
+
 def test_gate_activation_elementwise(g, oracle):
     # rows of length 1: c is alpha itself, so the activation is checked element by element, over
     # pre-activations from deeply negative (alpha ~ e^z, where the rounding of 1 + e^z would show) to large
