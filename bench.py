@@ -125,6 +125,9 @@ def main() -> int:
                     help="time only the memory-bound gate kernels (prefix scan, fused activation + prefix scan, "
                          "gate-gradient scan, activation backward) on [B,H,N] fp32 tensors of this shape, "
                          "e.g. 16,64,262144 (1 GiB per tensor), and print their GB/s instead of the usual line")
+    ap.add_argument("--min-workspace", action="store_true",
+                    help="give the backward its minimum workspace (the variant that forms S and dP in both passes) "
+                         "instead of gfwa_backward_fast_workspace_bytes")
     ap.add_argument("--cpu-heads", type=int, default=32)
     ap.add_argument("--traffic-file", default=None,
                     help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: lines "
@@ -176,7 +179,8 @@ def main() -> int:
     if wl.backward:
         dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
         dalpha = torch.empty_like(alpha)
-        ws = torch.empty(g.gfwa_backward_workspace_bytes(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=dev)
+        ws_size = g.gfwa_backward_workspace_bytes if args.min_workspace else g.gfwa_backward_fast_workspace_bytes
+        ws = torch.empty(ws_size(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=dev)
 
     gqa = wl.Hkv != wl.H   # grouped-query workloads go through the entry points that take [B,Hkv,N,d] keys
     fwd, bwd = (g.gfwa_forward_gqa, g.gfwa_backward_gqa) if gqa else (g.gfwa_forward, g.gfwa_backward)
@@ -300,7 +304,8 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: B={B} H={H}" + (f" Hkv={wl.Hkv}" if gqa else "") + f" N={N} d={d} w={w} {wl.dtype}, "
                    + ("gate activation + prefix" if args.from_preactivation else "gate prefix") + " + forward"
                    + (" + backward" if wl.backward else "")
-                   + (" + gate activation backward" if args.from_preactivation and wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS},
+                   + (" + gate activation backward" if args.from_preactivation and wl.backward else ""), "peak_bf16_tflops": PEAK_BF16_TFLOPS,
+                   "backward_workspace_mb": round(ws.numel() / 1e6, 1) if wl.backward else None},
         "roofline": roofline, "cpu_baseline": cpu, "detail": detail, "kernels": kernels,
     }
     print(json.dumps(out))

@@ -107,8 +107,15 @@ int gfwa_forward(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, c
                  void *O, float *L, int B, int H, int N, int d, int w, float scale,
                  gfwa_stream_t stream);
 
-/* Bytes of device scratch gfwa_backward needs for these sizes (0 on invalid sizes). */
+/* Bytes of device scratch gfwa_backward needs at least for these sizes (0 on invalid sizes). */
 size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w);
+/*
+ * Bytes of device scratch with which gfwa_backward runs its faster variant (0 on invalid sizes; equal to
+ * gfwa_backward_workspace_bytes where there is no such variant: fp32, d = 64).  The variant keeps the dS
+ * blocks of App. E.2 the dK/dV pass forms (bf16, about 2 (w + 48) bytes per token and head) for the dQ pass
+ * instead of forming S and dP twice; same outputs to the rounding of dS, which both passes apply anyway.
+ */
+size_t gfwa_backward_fast_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w);
 
 /*
  * Backward (paper App. E.2, Alg. 3, plus the chain-rule factor `scale` on dQ and dK and the
@@ -124,7 +131,8 @@ size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d
  * Inputs: Q,K,V,O,dO [B,H,N,d] of dtype `dt` (O and L as written by gfwa_forward), c, L [B,H,N] fp32.
  * Outputs: dQ,dK,dV [B,H,N,d] of dtype `dt`; dalpha [B,H,N] fp32.
  * workspace: device scratch of at least gfwa_backward_workspace_bytes(...) bytes, 16-byte
- * aligned, contents undefined before and after the call.
+ * aligned, contents undefined before and after the call; with workspace_bytes >=
+ * gfwa_backward_fast_workspace_bytes(...) the faster variant runs.
  */
 int gfwa_backward(gfwa_dtype_t dt, const void *Q, const void *K, const void *V, const void *O,
                   const void *dO, const float *c, const float *L, void *dQ, void *dK, void *dV,

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     GfwaError,
     gfwa_backward,
     gfwa_backward_gqa,
+    gfwa_backward_fast_workspace_bytes,
     gfwa_backward_workspace_bytes,
     gfwa_decode,
     gfwa_decode_workspace_bytes,

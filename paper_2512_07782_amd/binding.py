@@ -18,7 +18,7 @@ _lib: Optional[ctypes.CDLL] = None
 
 GFWA_BF16, GFWA_F32 = 0, 1
 
-EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward",
+EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_backward",
            "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes", "gfwa_gate_prefix_stp",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
@@ -55,6 +55,8 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_forward.restype = i
     lib.gfwa_backward_workspace_bytes.argtypes = [i, i, i, i, i, i]
     lib.gfwa_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.gfwa_backward_fast_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.gfwa_backward_fast_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_backward.argtypes = [i, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, ctypes.c_size_t,
                                   i, i, i, i, i, f, vp]
     lib.gfwa_backward.restype = i
@@ -226,9 +228,17 @@ def gfwa_backward_workspace_bytes(dtype: torch.dtype, B: int, H: int, N: int, d:
     return int(load_library().gfwa_backward_workspace_bytes(dt, B, H, N, d, int(w)))
 
 
+def gfwa_backward_fast_workspace_bytes(dtype: torch.dtype, B: int, H: int, N: int, d: int, w: int) -> int:
+    dt = GFWA_BF16 if dtype == torch.bfloat16 else GFWA_F32
+    return int(load_library().gfwa_backward_fast_workspace_bytes(dt, B, H, N, d, int(w)))
+
+
 def gfwa_backward(Q, K, V, O, dO, c, L, w: int, scale: float, workspace: Optional[torch.Tensor] = None,
                   dQ=None, dK=None, dV=None, dalpha=None):
-    """dQ, dK, dV ([B,H,N,d], dtype of Q) and dalpha ([B,H,N] fp32) from the saved O and L."""
+    """dQ, dK, dV ([B,H,N,d], dtype of Q) and dalpha ([B,H,N] fp32) from the saved O and L.
+
+    workspace: None allocates the minimum; a tensor of gfwa_backward_fast_workspace_bytes selects the
+    faster variant of the library (the same holds for gfwa_backward_gqa)."""
     if Q.dim() != 4:
         raise ValueError("Q must be [B,H,N,d]")
     B, H, N, d = Q.shape

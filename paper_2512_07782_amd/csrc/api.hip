@@ -136,6 +136,12 @@ size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d
     return 3 * one;
 }
 
+size_t gfwa_backward_fast_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
+    const size_t base = gfwa_backward_workspace_bytes(dt, B, H, N, d, w);
+    if (base == 0 || dt != GFWA_BF16) return base;
+    return base + backward_bf16_spill_bytes(B, H, N, d, w);
+}
+
 int gfwa_backward(gfwa_dtype_t dt, const void* Q, const void* K, const void* V, const void* O,
                   const void* dO, const float* c, const float* L, void* dQ, void* dK, void* dV,
                   float* dalpha, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, int w,
@@ -164,8 +170,10 @@ int gfwa_backward_gqa(gfwa_dtype_t dt, const void* Q, const void* K, const void*
         return hip_status(backward_f32((const float*)Q, (const float*)K, (const float*)V, (const float*)O,
                                        (const float*)dO, c, L, (float*)dQ, (float*)dK, (float*)dV, dalpha,
                                        ws, B, H, Hkv, N, d, w, scale, stream));
+    const size_t fast = gfwa_backward_fast_workspace_bytes(dt, B, H, N, d, w);
+    const bool spill = fast > need && workspace_bytes >= fast;
     return hip_status(
-        backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, d, w, scale, stream));
+        backward_bf16(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, spill, B, H, Hkv, N, d, w, scale, stream));
 }
 
 size_t gfwa_decode_workspace_bytes(int B, int H, int T, int d, int w) {

@@ -126,23 +126,27 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
         const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
         float colsum = 0.f;
         // per-row vectors of query tile i, one row per thread of the first wave
-        float nl_stage = -kPosBig, d_stage = 0.f;
+        // (the loaded values are only touched in store_vec, a tile later: arithmetic on them right here
+        // would make the first wave wait for them, and for the tile loads issued just before, in every tile)
+        float l_stage = kPosBig, c_stage = 0.f, d_stage = 0.f;
         auto load_vec = [&](int i) {
             if (tid < kTileRows) {
                 const int t = i * kTileRows + tid;
                 if (t < N) {
-                    nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
-                    d_stage = -Dh[t];
+                    l_stage = Lh[t];
+                    c_stage = ch[t];
+                    d_stage = Dh[t];
                 } else {
-                    nl_stage = -kPosBig;
+                    l_stage = kPosBig;
+                    c_stage = cbase;
                     d_stage = 0.f;
                 }
             }
         };
         auto store_vec = [&](int buf) {
             if (tid < kTileRows) {
-                sm.nl[buf][tid] = nl_stage;
-                sm.dvec[buf][tid] = d_stage;
+                sm.nl[buf][tid] = -(l_stage + (c_stage - cbase)) * inv_scale;
+                sm.dvec[buf][tid] = -d_stage;
             }
         };
         loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
@@ -153,9 +157,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
 
         for (int i = i_lo; i <= i_hi; ++i) {
             const int buf = (i - i_lo) & 1;
-            if (i < i_hi) {
-                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
+            if (i < i_hi) {  // the plain loads first: whatever wait the compiler puts in front of them must not cover the tile loads
                 load_vec(i + 1);
+                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
             }
             const char* qt = sm.qg.a[buf];
             const char* gt = sm.qg.b[buf];
@@ -260,6 +264,22 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
     }
 }
 
+// dS spill (d = 128, optional).  With a workspace of N x (w + 32..63) bf16 per head the dK/dV kernel also
+// stores the dS blocks it forms, and dQ = dS K is computed from them by a kernel that reads them back
+// instead of forming S and dP a second time: 5 executed matrix products instead of 7, for
+// 2 x 2 KB of memory traffic per 32 x 32 block.  Layout: block (head bh, 32-query block qb, 32-key block kb)
+// lives at slot kb - qb + nslot - 1 of the nslot = (w + 30) / 32 + 1 slots of (bh, qb); a block is two
+// pieces of 1 KB (query halves c2 = 0, 1 of the block); piece c2 holds, for key k of the block and
+// register half h, the 16 bytes  dS[q = 16 c2 + 4 h + 0..3][k], dS[q = 16 c2 + 8 + 4 h + 0..3][k]  (exactly the
+// B-operand fragment of the dK product) at 16-byte slot 32 h + k, i.e. in lane order: a store writes 1 KB
+// front to back.  The reader permutes while it copies a piece into LDS (slot (2 k + h + 8 c2) mod 64 there), so
+// that a transposing LDS read of 4 keys x 16 queries touches 128 contiguous bytes.
+__host__ __device__ inline int ds_spill_slots(int w, int nqb) {
+    const long s = ((long)w + 30) / 32 + 1;
+    return (int)(s < nqb ? s : nqb);
+}
+constexpr int kSpillBlockBytes = 2048;
+
 // 8-wave variant (d = 128): two waves per SIMD.  The workgroup still owns 128 keys, but the waves kg
 // and kg + 4, which share a SIMD, both work on key group kg and take one of the two 32-query blocks
 // of every tile each, so that one wave's MFMAs run while the other does its softmax arithmetic or
@@ -277,12 +297,13 @@ struct Dkv8Smem {
     float colred[4][32];
 };
 
-template <int D>
+template <int D, bool SPILL>
 __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ c, const float* __restrict__ L,
     const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
-    float* __restrict__ dc_col, int N, int w, float scale, int num_ktiles, int total_tiles, int H, int G) {
+    float* __restrict__ dc_col, char* __restrict__ ds_ws, int N, int w, float scale, int num_ktiles,
+    int total_tiles, int H, int G) {
     constexpr int BK = 128;  // keys per workgroup, 32 per wave
     constexpr int KC = D / 16, DB = D / 32;
     __shared__ Dkv8Smem<D> sm8;
@@ -325,6 +346,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
     const int i_lo = k0 / kTileRows, i_hi = t_hi / kTileRows;
     const int ifull = N / kTileRows;
 
+    // dS spill: 32-query blocks per head, slots per query block, this lane's 16-byte slot in the two pieces
+    const int nqb = (N + 31) / 32;
+    const int nslot = ds_spill_slots(w, nqb);
+    const int spill_lane0 = 16 * lane, spill_lane1 = 1024 + 16 * lane;
+
     TilePairLoader<D, 8> loader;
     loader.init(wv, lane);
     {  // K and V of the 128 keys; the wait and barrier in front of the first query tile cover them
@@ -345,23 +371,31 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
         const float ckl = (ch[min(key, N - 1)] - cbase) * kLog2e;  // lane-constant part of the exponent
         float colsum = 0.f;
         // per-row vectors of query tile i, one row per thread of the first wave
-        float nl_stage = -kPosBig, d_stage = 0.f;
+        // (the loaded values are only touched in store_vec, a tile later: arithmetic on them right here
+        // would make the first wave wait for them, and for the tile loads issued just before, in every tile)
+        float l_stage = kPosBig, c_stage = 0.f, d_stage = 0.f;
         auto load_vec = [&](int i) {
             if (tid < kTileRows) {
-                const int t = i * kTileRows + tid;
+                // (per-lane values that only rare paths need are re-derived in place, see GFWA_PIN, rather
+                // than carried through the tile loop as one more induction register each)
+                int tid_l = tid;
+                GFWA_PIN(tid_l);
+                const int t = i * kTileRows + tid_l;
                 if (t < N) {
-                    nl_stage = -(Lh[t] + (ch[t] - cbase)) * inv_scale;
-                    d_stage = -Dh[t];
+                    l_stage = Lh[t];
+                    c_stage = ch[t];
+                    d_stage = Dh[t];
                 } else {
-                    nl_stage = -kPosBig;
+                    l_stage = kPosBig;
+                    c_stage = cbase;
                     d_stage = 0.f;
                 }
             }
         };
         auto store_vec = [&](int buf) {
             if (tid < kTileRows) {
-                sm.nl[buf][tid] = nl_stage;
-                sm.dvec[buf][tid] = d_stage;
+                sm.nl[buf][tid] = -(l_stage + (c_stage - cbase)) * inv_scale;
+                sm.dvec[buf][tid] = -d_stage;
             }
         };
         loader.load(Qh, Gh, i_lo, ifull, N, sm.qg.a[0], sm.qg.b[0]);
@@ -372,16 +406,18 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
 
         for (int i = i_lo; i <= i_hi; ++i) {
             const int buf = (i - i_lo) & 1;
-            if (i < i_hi) {
-                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
+            if (i < i_hi) {  // the plain loads first: whatever wait the compiler puts in front of them must not cover the tile loads
                 load_vec(i + 1);
+                loader.load(Qh, Gh, i + 1, ifull, N, sm.qg.a[buf ^ 1], sm.qg.b[buf ^ 1]);
             }
             const char* qt = sm.qg.a[buf];
             const char* gt = sm.qg.b[buf];
+            bool stored = false, vec_done = false;
             {
                 const int sb = half;
                 const int qb0 = i * kTileRows + 32 * sb;
                 const bool act = (kw0 <= qb0 + 31) && (kw0 + 31 > qb0 - w) && (kw0 < N) && (qb0 < N);
+                stored = act;
                 if (act) {
                 const bool full = (kw0 + 31 <= qb0) && (kw0 > qb0 + 31 - w);
 
@@ -423,9 +459,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(s[v], sl, ckl));
                 if (!full) {
+                    int h_l = h;
+                    GFWA_PIN(h_l);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int t = qb0 + acc_row(v, h);
+                        const int t = qb0 + acc_row(v, h_l);
                         const bool keep = (key <= t) && (key > t - w);
                         p[v] = keep ? p[v] : 0.f;
                     }
@@ -433,11 +471,31 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     ds[v] = p[v] * dp[v];
-                    colsum += ds[v];
+                    if (!SPILL) colsum += ds[v];
+                }
+                // (the first wave hands over the row vectors of the next tile here, before the stores below:
+                // the wait in front of their first use would otherwise cover the stores too)
+                if (SPILL && i < i_hi) {
+                    store_vec(buf ^ 1);
+                    vec_done = true;
                 }
                 bf16x8 pf[2], dsf[2];
                 acc_to_bfrag(p, pf);
                 acc_to_bfrag(ds, dsf);
+                if (SPILL) {
+                    // the column sums take the rounded values the dQ kernel will sum along the rows, so that
+                    // the two cancel exactly in the suffix sums of the gate gradient; then the block is stored
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) colsum += (float)dsf[c2][e];
+                    const int qb = 2 * i + sb, kb = kw0 >> 5;
+                    char* blk = ds_ws + (((size_t)bh * nqb + qb) * nslot + (kb - qb + nslot - 1)) * kSpillBlockBytes;
+                    // streaming stores: the blocks are read once, by the next kernel, and must not push the
+                    // Q and dO tiles the neighbouring workgroups are about to re-read out of the L2
+                    __builtin_nontemporal_store(dsf[0], reinterpret_cast<bf16x8*>(blk + spill_lane0));
+                    __builtin_nontemporal_store(dsf[1], reinterpret_cast<bf16x8*>(blk + spill_lane1));
+                }
                 if (D != 128) {
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2)
@@ -453,6 +511,8 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                         const int c2 = f / (2 * DB), db = (f / 2) % DB;
                         fr[f] = lds_read_tr_frag<D>((f & 1) ? qt : gt, 32 * sb + 16 * c2, db, lane);
                     };
+                    // the two stores of a spilled block go first: their latency hides behind the 16 MFMAs
+                    if (SPILL) __builtin_amdgcn_sched_group_barrier(0x040, 2, 0);
 #pragma unroll
                     for (int f = 0; f < kAhead; ++f) fetch(f);
                     __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
@@ -470,9 +530,12 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                 }
                 }
             }
-            if (i < i_hi) store_vec(buf ^ 1);
-            __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile i+1 has landed
-            __syncthreads();
+            if (i < i_hi && !vec_done) store_vec(buf ^ 1);
+            // this wave's share of tile i+1 has landed; the two stores of a spilled block were issued after
+            // those loads and may stay in flight
+            if (SPILL && stored) __builtin_amdgcn_s_waitcnt(vmcnt_only(2));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+            wg_barrier();  // not __syncthreads: its fence would wait for the stores as well
         }
 
         // column sums of the two query halves
@@ -594,21 +657,21 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
 
     TilePairLoader<D> loader;
     loader.init(wv, lane);
-    auto gate_of = [&](int j) {  // this thread's g value of tile j (threads 0..63)
+    auto gate_of = [&](int j) {  // this thread's c value of tile j (threads 0..63)
         const int key = min(j * kTileRows + tid, N - 1);
-        return (ch[key] - cbase) * inv_scale;
+        return ch[key];
     };
     loader.load(Kh, Vh, j_lo, jfull, N, sm.kv.a[0], sm.kv.b[0]);
-    if (tid < kTileRows) sm.g[0][tid] = gate_of(j_lo);
+    if (tid < kTileRows) sm.g[0][tid] = (gate_of(j_lo) - cbase) * inv_scale;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int j = j_lo; j <= j_hi; ++j) {
         const int buf = (j - j_lo) & 1;
         float g_next = 0.f;
-        if (j < j_hi) {
-            loader.load(Kh, Vh, j + 1, jfull, N, sm.kv.a[buf ^ 1], sm.kv.b[buf ^ 1]);
+        if (j < j_hi) {  // the plain load first: whatever wait the compiler puts in front of it must not cover the tile loads
             if (tid < kTileRows) g_next = gate_of(j + 1);
+            loader.load(Kh, Vh, j + 1, jfull, N, sm.kv.a[buf ^ 1], sm.kv.b[buf ^ 1]);
         }
         const char* kt = sm.kv.a[buf];
         const char* vt = sm.kv.b[buf];
@@ -683,7 +746,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
                 }
             }
         }
-        if (j < j_hi && tid < kTileRows) sm.g[buf ^ 1][tid] = g_next;
+        // (g_next is first touched here, a tile after its load was issued, so nothing waits for it earlier)
+        if (j < j_hi && tid < kTileRows) sm.g[buf ^ 1][tid] = (g_next - cbase) * inv_scale;
         __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's share of tile j+1 has landed
         __syncthreads();
     }
@@ -703,15 +767,159 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// 3b. dQ and row sums from spilled dS blocks (d = 128): one matrix product, no exponentials
+// ------------------------------------------------------------------------------------------
+// Query-stationary like the kernel above (a lane owns one query, a wave 32 of them, K tiles of 64 keys
+// stream through LDS), but S and dP are not formed again: the dS^T fragments (B operands: column =
+// query, k = key) are read back from the blocks the dK/dV kernel stored.  A block travels global -> LDS
+// unchanged; a transposing LDS read then hands a lane the dS of its query for four keys.
+template <int D>
+struct DqSpillSmem {
+    alignas(16) char k[2][kTileRows * D * 2];                        // K tile
+    alignas(16) char ds[2][kThreads / 64][2][kSpillBlockBytes];      // [buffer][wave][32-key block of the tile]
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void bwd_dq_spill_bf16_kernel(
+    const bf16_t* __restrict__ K, const char* __restrict__ ds_ws, bf16_t* __restrict__ dQ,
+    float* __restrict__ dc_row, int N, int w, float scale, int num_qtiles, int total_tiles, int H, int G) {
+    constexpr int BR = 128;
+    constexpr int DB = D / 32;
+    extern __shared__ __align__(16) char smem_raw[];
+    DqSpillSmem<D>& sm = *reinterpret_cast<DqSpillSmem<D>*>(smem_raw);
+
+    const int tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bh = tile / num_qtiles;
+    const int q0 = (tile % num_qtiles) * BR;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, lq = lane & 31;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const char* Kh = reinterpret_cast<const char*>(K + (size_t)kv_head_of(bh, H, G) * N * D);
+    const int qw0 = q0 + 32 * wv;
+    const int t = qw0 + lq;
+    const int nqb = (N + 31) / 32;
+    const int nslot = ds_spill_slots(w, nqb);
+    const int qb = qw0 >> 5;
+    // slots of this wave's query block (read only for blocks inside the band, which implies qw0 < N)
+    const char* blk0 = ds_ws + ((size_t)bh * nqb + qb) * nslot * kSpillBlockBytes;
+
+    // byte offsets of this lane's transposing reads inside a block: 16-key chunk cc, read rd (keys
+    // 16 cc + 4 h + 0..3, then 16 cc + 8 + 4 h + 0..3: the order in which lds_read_tr_frag hands out rows).
+    // In its group of 16 lanes, lane j supplies the 8 bytes of key (j >> 2), query group (j & 3), and
+    // receives query j of the group for the four keys.
+    int ds_off[2][2];
+    {
+        const int c2 = lq >> 4, j = lane & 15, r = j >> 2, cg = j & 3;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd) {
+                const int key = 16 * cc + 8 * rd + 4 * h + r;
+                ds_off[cc][rd] = 1024 * c2 + 16 * ((2 * key + (cg & 1) + 8 * c2) & 63) + 8 * (cg >> 1);
+            }
+    }
+
+    // LDS slot p of piece c2 takes (key, h) with 2 key + h = (p - 8 c2) mod 64, stored at slot 32 h + key
+    const unsigned gather0 = 16u * (32u * (lane & 1) + (lane >> 1));
+    const unsigned gather1 = 1024u + 16u * (32u * (((lane - 8) & 63) & 1) + (((lane - 8) & 63) >> 1));
+
+    f32x16 dq_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dq_acc[db][v] = 0.f;
+    float rowsum = 0.f;
+
+    const int k_lo = max(0, q0 - w + 1);
+    const int k_hi = min(N, q0 + BR) - 1;
+    const int j_lo = k_lo / kTileRows, j_hi = k_hi / kTileRows;
+    const int jfull = N / kTileRows;
+    auto in_band = [&](int kb0) { return (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N); };
+
+    TilePairLoader<D> loader;
+    loader.init(wv, lane);
+    auto issue = [&](int j, int buf) {
+        loader.load_one(Kh, j, jfull, N, sm.k[buf]);
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+            const int kb0 = j * kTileRows + 32 * sb;
+            if (in_band(kb0)) {
+                const char* src = blk0 + (size_t)((kb0 >> 5) - qb + nslot - 1) * kSpillBlockBytes;
+                dma16_stream(src, gather0, sm.ds[buf][wv][sb]);
+                dma16_stream(src, gather1, sm.ds[buf][wv][sb] + 1024);
+            }
+        }
+    };
+    issue(j_lo, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    for (int j = j_lo; j <= j_hi; ++j) {
+        const int buf = (j - j_lo) & 1;
+        if (j < j_hi) issue(j + 1, buf ^ 1);
+        const char* kt = sm.k[buf];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+            if (!in_band(j * kTileRows + 32 * sb)) continue;
+            const char* blk = sm.ds[buf][wv][sb];
+            bf16x8 dsf[2];
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(blk + ds_off[cc][0]));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(blk + ds_off[cc][1]));
+                typedef short s16x8 __attribute__((ext_vector_type(8)));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                dsf[cc] = __builtin_bit_cast(bf16x8, both);
+            }
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    dq_acc[db] = mfma32(lds_read_tr_frag<D>(kt, 32 * sb + 16 * cc, db, lane), dsf[cc], dq_acc[db]);
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rowsum += (float)dsf[cc][e];
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's loads of tile j+1 have landed
+        __syncthreads();
+    }
+
+    const float rs = xhalf_sum(rowsum);
+    if (t < N) {
+        bf16_t* row = dQ + head_off + (size_t)t * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale, dq_acc[db][4 * g + 2] * scale,
+                            dq_acc[db][4 * g + 3] * scale};
+                *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(q4, bf16x4);
+            }
+        if (h == 0) dc_row[(size_t)bh * N + t] = rs;
+    }
+}
+
+size_t backward_bf16_spill_bytes(int B, int H, int N, int d, int w) {
+    if (d != 128) return 0;
+    const int nqb = (N + 31) / 32;
+    return (size_t)B * H * nqb * ds_spill_slots(w, nqb) * kSpillBlockBytes;
+}
+
 template <int D>
 static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                              const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                             float* ws, int B, int H, int Hkv, int N, int w, float scale, hipStream_t s) {
+                             float* ws, bool spill, int B, int H, int Hkv, int N, int w, float scale,
+                             hipStream_t s) {
     const size_t rows = (size_t)B * H * N;
     const size_t pad = ((rows * sizeof(float) + 255) & ~(size_t)255) / sizeof(float);
     float* Dv = ws;
     float* dc_col = ws + pad;
     float* dc_row = ws + 2 * pad;
+    char* ds_ws = reinterpret_cast<char*>(ws + 3 * pad);  // only with `spill`
     constexpr int LPR = D / 8;
     const unsigned dot_blocks = (unsigned)((rows * LPR + 255) / 256);
     {
@@ -722,11 +930,16 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     const int nk = (N + 127) / 128;
     {
         ProfScope prof(kKernDkv, s);
-        if constexpr (D == 128)  // two waves per SIMD that share a key group (at d = 64 the 4-wave kernel has them already)
-            hipLaunchKernelGGL((bwd_dkv8_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(2 * kThreads), 0, s,
-                               (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
-                               (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
-        else
+        if constexpr (D == 128) {  // two waves per SIMD that share a key group (at d = 64 the 4-wave kernel has them already)
+            if (spill)
+                hipLaunchKernelGGL((bwd_dkv8_bf16_kernel<D, true>), dim3(B * Hkv * nk), dim3(2 * kThreads), 0, s,
+                                   (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                                   (bf16_t*)dK, (bf16_t*)dV, dc_col, ds_ws, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
+            else
+                hipLaunchKernelGGL((bwd_dkv8_bf16_kernel<D, false>), dim3(B * Hkv * nk), dim3(2 * kThreads), 0, s,
+                                   (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                                   (bf16_t*)dK, (bf16_t*)dV, dc_col, ds_ws, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
+        } else
             hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), dim3(B * Hkv * nk), dim3(kThreads), 0, s,
                                (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
                                (bf16_t*)dK, (bf16_t*)dV, dc_col, N, w, scale, nk, B * Hkv * nk, H, H / Hkv);
@@ -734,9 +947,27 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     const int nq = (N + 127) / 128;
     {
         ProfScope prof(kKernDq, s);
-        hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads), 0, s,
-                           (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
-                           (bf16_t*)dQ, dc_row, N, w, scale, nq, B * H * nq, H, H / Hkv);
+        bool launched = false;
+        if constexpr (D == 128) {
+            if (spill) {
+                static bool attr_set = false;
+                if (!attr_set) {
+                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dq_spill_bf16_kernel<D>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)sizeof(DqSpillSmem<D>));
+                    if (e != hipSuccess) return e;
+                    attr_set = true;
+                }
+                hipLaunchKernelGGL((bwd_dq_spill_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads),
+                                   sizeof(DqSpillSmem<D>), s, (const bf16_t*)K, ds_ws, (bf16_t*)dQ, dc_row, N, w,
+                                   scale, nq, B * H * nq, H, H / Hkv);
+                launched = true;
+            }
+        }
+        if (!launched)
+            hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads), 0, s,
+                               (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, c, L, Dv,
+                               (bf16_t*)dQ, dc_row, N, w, scale, nq, B * H * nq, H, H / Hkv);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -745,9 +976,11 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
 
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                          const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s) {
-    if (d == 128) return launch_bwd<128>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, w, scale, s);
-    return launch_bwd<64>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, B, H, Hkv, N, w, scale, s);
+                         float* ws, bool spill, int B, int H, int Hkv, int N, int d, int w, float scale,
+                         hipStream_t s) {
+    if (d == 128)
+        return launch_bwd<128>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, spill, B, H, Hkv, N, w, scale, s);
+    return launch_bwd<64>(Q, K, V, O, dO, c, L, dQ, dK, dV, dalpha, ws, false, B, H, Hkv, N, w, scale, s);
 }
 
 }  // namespace gfwa

@@ -119,6 +119,16 @@ __device__ __forceinline__ void dma16(const void* sbase, unsigned voff, const vo
         : "s"(lds_addr), "v"(voff), "s"(sbase)
         : "memory");
 }
+// the same for data that is read once (non-temporal: first in line for eviction from the caches)
+__device__ __forceinline__ void dma16_stream(const void* sbase, unsigned voff, const void* lds_base) {
+    const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;
+    unsigned saved;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt\n\ts_mov_b32 m0, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(sbase)
+        : "memory");
+}
 __device__ __forceinline__ void dma4(const void* sbase, unsigned voff, const void* lds_base) {
     const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;
     unsigned saved;

@@ -27,10 +27,13 @@ hipError_t forward_bf16(const void* Q, const void* K, const void* V, const float
 hipError_t forward_f32(const float* Q, const float* K, const float* V, const float* c, float* O,
                        float* L, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 
-// Workspace layout of the backward: three fp32 vectors of B*H*N: D, dc_col, dc_row.
+// Workspace layout of the backward: three fp32 vectors of B*H*N (each padded to 256 bytes): D, dc_col,
+// dc_row; with `spill` (bf16, d = 128 only) backward_bf16_spill_bytes() more for the dS blocks.
+size_t backward_bf16_spill_bytes(int B, int H, int N, int d, int w);  // 0: no such variant for this shape
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                          const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
-                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
+                         float* ws, bool spill, int B, int H, int Hkv, int N, int d, int w, float scale,
+                         hipStream_t s);
 hipError_t backward_f32(const float* Q, const float* K, const float* V, const float* O, const float* dO,
                         const float* c, const float* L, float* dQ, float* dK, float* dV, float* dalpha,
                         float* ws, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);

@@ -54,14 +54,33 @@ struct TilePairLoader {
                 dma16(Bh + toff, off[g], bl + g * 1024);
             }
         } else {
+            int ln = lane;  // re-derived here (a rare path) instead of living in registers across the caller's loop
+            GFWA_PIN(ln);
+#pragma unroll
+            for (int g = 0; g < kLoadsPerWave; ++g) {
+                const int row = kRowsPerWave * wv + kRowsPerLoad * g + ln / kChunksPerRow;
+                const int r = min(j * kTileRows + row, N - 1);
+                const unsigned o =
+                    (unsigned)r * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, ln % kChunksPerRow) * 16);
+                dma16(Ah, o, al + g * 1024);
+                dma16(Bh, o, bl + g * 1024);
+            }
+        }
+    }
+    // one tile only (the A side of load)
+    __device__ __forceinline__ void load_one(const char* Ah, int j, int jfull, int N, char* a_tile) const {
+        char* al = a_tile + kRowsPerWave * wv * kRowBytes;
+        if (j < jfull) {
+            const size_t toff = (size_t)j * (kTileRows * kRowBytes);
+#pragma unroll
+            for (int g = 0; g < kLoadsPerWave; ++g) dma16(Ah + toff, off[g], al + g * 1024);
+        } else {
 #pragma unroll
             for (int g = 0; g < kLoadsPerWave; ++g) {
                 const int row = kRowsPerWave * wv + kRowsPerLoad * g + lane / kChunksPerRow;
                 const int r = min(j * kTileRows + row, N - 1);
-                const unsigned o =
-                    (unsigned)r * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, lane % kChunksPerRow) * 16);
-                dma16(Ah, o, al + g * 1024);
-                dma16(Bh, o, bl + g * 1024);
+                dma16(Ah, (unsigned)r * (unsigned)kRowBytes + (unsigned)(swz_chunk<D>(row, lane % kChunksPerRow) * 16),
+                      al + g * 1024);
             }
         }
     }

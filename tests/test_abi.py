@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
-                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes",
                             "gfwa_gate_prefix_stp",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
@@ -100,6 +100,16 @@ def test_argument_validation_on_host(lib):
     assert need >= 3 * 2 * 3 * 100 * 4
     assert lib.gfwa_backward_workspace_bytes(0, 2, 3, 100, 80, 16) == 0
     assert lib.gfwa_backward_workspace_bytes(0, 0, 3, 100, 64, 16) == 0
+    # the faster variant's workspace: the minimum plus, for bf16 at d = 128, 2 KB per 32x32 block of the band
+    # (per head: 4 query blocks of 32, each with min((16 + 30) // 32 + 1, 4) = 2 key-block slots)
+    lib.gfwa_backward_fast_workspace_bytes.argtypes = lib.gfwa_backward_workspace_bytes.argtypes
+    lib.gfwa_backward_fast_workspace_bytes.restype = ctypes.c_size_t
+    base128 = lib.gfwa_backward_workspace_bytes(0, 2, 3, 100, 128, 16)
+    assert lib.gfwa_backward_fast_workspace_bytes(0, 2, 3, 100, 128, 16) == base128 + 6 * 4 * 2 * 2048
+    assert lib.gfwa_backward_fast_workspace_bytes(0, 2, 3, 100, 64, 16) == need
+    assert lib.gfwa_backward_fast_workspace_bytes(1, 2, 3, 100, 128, 16) == lib.gfwa_backward_workspace_bytes(1, 2, 3, 100, 128, 16)
+    assert lib.gfwa_backward_fast_workspace_bytes(0, 2, 3, 100, 128, 1 << 30) == base128 + 6 * 4 * 4 * 2048
+    assert lib.gfwa_backward_fast_workspace_bytes(0, 0, 3, 100, 128, 16) == 0
     bargs = lambda **kw: [0] + [kw.get("Q", good)] + [good] * 10 + [kw.get("ws", good), kw.get("wsb", need),
                                                                    2, 3, 100, kw.get("d", 64), 16, f, None]
     assert lib.gfwa_backward(*bargs(Q=None)) == -1

@@ -58,6 +58,24 @@ def note(*a):
     print(*a, flush=True)
 
 
+# which workspace the backward calls of run_backward / run_gqa get: the minimum, or the size that selects
+# the library's faster variant (dS blocks kept for the dQ pass; bf16, d = 128)
+VARIANT = {"fast": False}
+
+
+@pytest.fixture(params=["min_ws", "fast_ws"])
+def ws_variant(request):
+    VARIANT["fast"] = request.param == "fast_ws"
+    yield request.param
+    VARIANT["fast"] = False
+
+
+def bwd_workspace(g, Q, w):
+    B, H, N, d = Q.shape
+    size = g.gfwa_backward_fast_workspace_bytes if VARIANT["fast"] else g.gfwa_backward_workspace_bytes
+    return torch.empty(size(Q.dtype, B, H, N, d, w), dtype=torch.uint8, device=Q.device)
+
+
 # ------------------------------------------------------------------------------------------
 # gate prefix
 # ------------------------------------------------------------------------------------------
@@ -357,7 +375,8 @@ def run_backward(g, oracle, wl, heads=None, chained=False):
         Od = dev(O_ref.astype(np.float32), "f32")
         Od = Od.to(torch.bfloat16) if wl.dtype == "bf16" else Od     # torch rounds to nearest even
         Ld = dev(L_ref.astype(np.float32), "f32")
-    dQ, dK, dV, dalpha = g.gfwa_backward(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale)
+    dQ, dK, dV, dalpha = g.gfwa_backward(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale,
+                                         workspace=bwd_workspace(g, Qd, wl.w))
     torch.cuda.synchronize()
     got = {"dQ": sel(host(dQ), 2), "dK": sel(host(dK), 2), "dV": sel(host(dV), 2), "dalpha": sel(host(dalpha), 1)}
     return got, ref
@@ -391,17 +410,17 @@ SMALL_BWD = [(1, 1, 1, 64, 1), (1, 2, 37, 64, 5), (2, 1, 129, 128, 1), (1, 2, 30
 
 @pytest.mark.parametrize("chained", [False, True])
 @pytest.mark.parametrize("B,H,N,d,w", SMALL_BWD)
-def test_backward_bf16_small(g, oracle, B, H, N, d, w, chained):
-    note("backward bf16 small", B, H, N, d, w, "chained", chained)
+def test_backward_bf16_small(g, oracle, ws_variant, B, H, N, d, w, chained):
+    note("backward bf16 small", ws_variant, B, H, N, d, w, "chained", chained)
     wl = gi.custom("bsmall", B, H, N, d, w, "bf16", alpha_mu=-1.0, index=12, backward=True)
     got, ref = run_backward(g, oracle, wl, chained=chained)
     check_grads(got, ref, 1e-2, "bf16")
 
 
 @pytest.mark.parametrize("name,heads", [("train_bwd", [0, 37, 63]), ("long_bwd", [5, 31])])
-def test_backward_bf16_full_size(g, oracle, name, heads):
+def test_backward_bf16_full_size(g, oracle, ws_variant, name, heads):
     wl = gi.WORKLOADS[name]
-    note("backward full size", wl)
+    note("backward full size", ws_variant, wl)
     got, ref = run_backward(g, oracle, wl, heads=heads)
     check_grads(got, ref, 1e-2, name)
 
@@ -414,10 +433,10 @@ MID = [  # several 256-query workgroups, many key tiles, ragged ends; sampled he
 
 
 @pytest.mark.parametrize("B,H,N,d,w,heads", MID)
-def test_forward_backward_bf16_mid_size(g, oracle, B, H, N, d, w, heads):
+def test_forward_backward_bf16_mid_size(g, oracle, ws_variant, B, H, N, d, w, heads):
     """Sizes between the small exhaustive cases and the benchmark workloads: multi-tile both ways,
     N not a multiple of any tile, windows below, at and above N."""
-    note("mid size", B, H, N, d, w)
+    note("mid size", ws_variant, B, H, N, d, w)
     wl = gi.custom("mid", B, H, N, d, w, "bf16", alpha_mu=-1.5, index=14, backward=True)
     O, L, O_ref, L_ref = run_forward(g, oracle, wl, heads=heads)
     check_bf16_forward(O, L, O_ref, L_ref, tag="mid")
@@ -437,7 +456,8 @@ def run_gqa(g, oracle, wl, groups=None):
     Qd, Kd, Vd, dOd = (dev(ins[t], wl.dtype) for t in ("Q", "K", "V", "dO"))
     cd = dev(c32, "f32")
     Od, Ld = g.gfwa_forward_gqa(Qd, Kd, Vd, cd, wl.w, wl.scale)
-    dQ, dK, dV, dalpha = g.gfwa_backward_gqa(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale)
+    dQ, dK, dV, dalpha = g.gfwa_backward_gqa(Qd, Kd, Vd, Od, dOd, cd, Ld, wl.w, wl.scale,
+                                             workspace=bwd_workspace(g, Qd, wl.w))
     torch.cuda.synchronize()
     assert dK.shape == Kd.shape and dV.shape == Vd.shape
     if groups is None:
@@ -473,8 +493,8 @@ GQA_BF16 = [(1, 4, 1, 300, 128, 64), (2, 8, 2, 515, 64, 512), (1, 4, 2, 1536, 12
 
 
 @pytest.mark.parametrize("B,H,Hkv,N,d,w", GQA_BF16)
-def test_gqa_bf16(g, oracle, B, H, Hkv, N, d, w):
-    note("gqa bf16", B, H, Hkv, N, d, w)
+def test_gqa_bf16(g, oracle, ws_variant, B, H, Hkv, N, d, w):
+    note("gqa bf16", ws_variant, B, H, Hkv, N, d, w)
     wl = gi.custom("gqa16", B, H, N, d, w, "bf16", alpha_mu=-1.0, index=14, backward=True, kv_heads=Hkv)
     got, ref = run_gqa(g, oracle, wl)
     check_bf16_forward(got["O"], got["L"], ref["O"], ref["L"], tag="gqa")
@@ -482,8 +502,8 @@ def test_gqa_bf16(g, oracle, B, H, Hkv, N, d, w):
 
 
 @pytest.mark.parametrize("name,groups", [("lm_gqa_bwd", [0, 7, 15]), ("long_gqa_bwd", [3])])
-def test_gqa_bf16_full_size(g, oracle, name, groups):
-    note("gqa full size", name, groups)
+def test_gqa_bf16_full_size(g, oracle, ws_variant, name, groups):
+    note("gqa full size", ws_variant, name, groups)
     got, ref = run_gqa(g, oracle, gi.WORKLOADS[name], groups=groups)
     check_bf16_forward(got["O"], got["L"], ref["O"], ref["L"], tag=name)
     check_grads(got, ref, 1e-2, name)
@@ -513,7 +533,7 @@ def test_forward_is_deterministic(g, oracle):
     assert torch.equal(O1, O2) and torch.equal(L1, L2)
 
 
-def test_backward_is_deterministic(g, oracle):
+def test_backward_is_deterministic(g, oracle, ws_variant):
     wl = gi.custom("det", 1, 2, 700, 128, 200, "bf16", alpha_mu=-1.0, index=13, backward=True)
     a, _ = run_backward(g, oracle, wl, chained=True)
     b, _ = run_backward(g, oracle, wl, chained=True)
@@ -623,10 +643,12 @@ def _random_shapes(n, seed):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_random_shapes_forward_backward(g, oracle, dtype):
+def test_random_shapes_forward_backward(g, oracle, ws_variant, dtype):
+    if dtype == "f32" and ws_variant == "fast_ws":
+        pytest.skip("fp32 storage has one variant")
     # seeded random shapes: ragged N, windows shorter and longer than the sequence, grouped heads
     for case, (B, H, Hkv, N, d, w) in enumerate(_random_shapes(28, 2512)):
-        note("random shape", case, (B, H, Hkv, N, d, w), dtype)
+        note("random shape", ws_variant, case, (B, H, Hkv, N, d, w), dtype)
         wl = gi.custom("rnd", B, H, N, d, w, dtype, alpha_mu=-1.0, index=28 + case % 4, backward=True, kv_heads=Hkv)
         got, ref = run_gqa(g, oracle, wl)
         if dtype == "bf16":
