@@ -246,7 +246,9 @@ def main() -> int:
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
     # measured HBM bytes per launch (fetch + write) of the dominant kernel, from the counter runs
     traffic = None
-    tfile = args.traffic_file or os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.txt")
+    # (the committed summary is of the default run: the backward with its dS-block workspace)
+    tfile = args.traffic_file or os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}"
+                                              + ("_min_workspace" if args.min_workspace else "") + ".txt")
     if os.path.exists(tfile):
         for line in open(tfile):
             f = line.split("#")[0].split()
