@@ -100,8 +100,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         Vh = reinterpret_cast<const char*>(V + kv_off);
         ch = c + (size_t)bh * N;
         cbase = ch[q0];
-        // the two waves of a SIMD take adjacent 32-query slabs, so their bands differ by one block
-        qw0 = q0 + 64 * (wv & 3) + 32 * grp;  // first query of this wave
+        // the two waves of a SIMD take slabs 128 queries apart: in the first and last key tiles of the band, where
+        // only the upper or the lower half of the queries has keys, every SIMD then still has one wave at work
+        qw0 = q0 + 32 * (wv & 3) + 128 * grp;  // first query of this wave
         t = qw0 + lq;
         {  // rows past N read row N-1
             const bf16_t* qp = Q + head_off + (size_t)min(t, N - 1) * D + 8 * h;
