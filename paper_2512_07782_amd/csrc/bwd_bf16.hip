@@ -314,8 +314,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
     const int k0 = (tile % num_ktiles) * BK;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kg = wv & 3;     // 32-key group; waves kg and kg + 4 share it (and a SIMD)
-    const int half = wv >> 2;  // ... and take one 32-query block of every tile each
+    // 32-key group kg and 32-query block `half` of every tile.  The two waves of a key group sit on different
+    // SIMDs (wave w runs on SIMD w % 4): in the tiles at the diagonal and at the far end of the window, where only
+    // some key groups have work, the active waves then spread over the SIMDs instead of pairing up on one.
+    const int half = wv >> 2;
+    const int kg = (wv + 2 * half) & 3;
     const int h = lane >> 5, lk = lane & 31;
     const float sl = scale * kLog2e;
     const float inv_scale = 1.0f / scale;
