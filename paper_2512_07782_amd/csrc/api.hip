@@ -43,6 +43,27 @@ struct ProfState {
 ProfState g_prof;
 }  // namespace
 
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes, DeviceOnce& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev < 64 && (__atomic_load_n(&done.bits, __ATOMIC_ACQUIRE) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev < 64) __atomic_fetch_or(&done.bits, bit, __ATOMIC_RELEASE);
+    return e;
+}
+
+int device_cu_count() {
+    static int cached[64];  // 0: not asked yet
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev >= 0 && dev < 64 && (n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED)) > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    if (dev >= 0 && dev < 64) __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+    return n;
+}
+
 ProfScope::ProfScope(int kernel, hipStream_t s) : slot_(-1), s_(s) {
     if (!g_prof.on || g_prof.used >= kMaxRecords) return;
     const int i = g_prof.used;

@@ -953,14 +953,10 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
         bool launched = false;
         if constexpr (D == 128) {
             if (spill) {
-                static bool attr_set = false;
-                if (!attr_set) {
-                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dq_spill_bf16_kernel<D>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       (int)sizeof(DqSpillSmem<D>));
-                    if (e != hipSuccess) return e;
-                    attr_set = true;
-                }
+                static DeviceOnce lds_allowed;
+                if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_spill_bf16_kernel<D>),
+                                                     sizeof(DqSpillSmem<D>), lds_allowed))
+                    return e;
                 hipLaunchKernelGGL((bwd_dq_spill_bf16_kernel<D>), dim3(B * H * nq), dim3(kThreads),
                                    sizeof(DqSpillSmem<D>), s, (const bf16_t*)K, ds_ws, (bf16_t*)dQ, dc_row, N, w,
                                    scale, nq, B * H * nq, H, H / Hkv);

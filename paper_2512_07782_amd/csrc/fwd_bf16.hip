@@ -393,20 +393,11 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
                              float* L, int B, int H, int Hkv, int N, int w, float scale, hipStream_t s) {
     const int num_qtiles = (N + kFwdBR - 1) / kFwdBR;
     const int total = B * H * num_qtiles;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(FwdSmem<D>));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    static int num_cu = 0;
-    if (num_cu == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cu <= 0)
-            num_cu = 256;
-    }
+    static DeviceOnce lds_allowed;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D>), sizeof(FwdSmem<D>),
+                                         lds_allowed))
+        return e;
+    const int num_cu = device_cu_count();
     const int grid = total < num_cu ? total : num_cu;  // one resident workgroup per CU
     ProfScope prof(kKernForward, s);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(grid), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,

@@ -50,6 +50,13 @@ enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernD
                 kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernScanSegmentSum,
                 kKernScanPropagate, kKernCount };
 
+// Per-device launch set-up, done once per device and kernel (`done`: one bit per device id, owned by the caller):
+// lets `kernel` use `bytes` of dynamic LDS on the current device.
+struct DeviceOnce { unsigned long long bits = 0; };
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes, DeviceOnce& done);
+// Compute units of the current device (256 if the query fails).
+int device_cu_count();
+
 // RAII pair of HIP events around one kernel launch on stream s; a no-op unless profiling is on.
 struct ProfScope {
     ProfScope(int kernel, hipStream_t s);
