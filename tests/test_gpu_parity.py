@@ -601,7 +601,7 @@ def test_step_under_graph_capture_replays_bit_exactly(g, oracle):
         torch.cuda.synchronize()
 
 
-def test_offsets_beyond_32_bits(g, oracle):
+def test_offsets_beyond_32_bits(g, oracle, ws_variant):
     # 2^31 elements per [B,H,N,d] tensor: element offsets of the last heads do not fit 32 bits.  Inputs
     # are drawn on the GPU (seeded); the oracle gets the first and the last head.
     B, H, N, d, w = 8, 32, 65536, 128, 64
@@ -613,7 +613,9 @@ def test_offsets_beyond_32_bits(g, oracle):
     scale = 1.0 / d ** 0.5
     c = g.gfwa_gate_prefix(alpha)
     O, L = g.gfwa_forward(Q, K, V, c, w, scale)
-    dQ, dK, dV, dalpha = g.gfwa_backward(Q, K, V, O, dO, c, L, w, scale)
+    ws = bwd_workspace(g, Q, w)   # with the dS blocks: 3.2 GB, block offsets of the last heads beyond 32 bits too
+    note("  workspace", ws_variant, ws.numel())
+    dQ, dK, dV, dalpha = g.gfwa_backward(Q, K, V, O, dO, c, L, w, scale, workspace=ws)
     torch.cuda.synchronize()
     for b, h in ((0, 0), (B - 1, H - 1)):
         note("  head", b, h)
