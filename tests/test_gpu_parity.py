@@ -559,7 +559,7 @@ def test_outputs_do_not_spill_past_their_buffers(g):
     assert not (O == 7.0).all()
 
 
-def test_step_under_graph_capture_replays_bit_exactly(g, oracle):
+def test_step_under_graph_capture_replays_bit_exactly(g, oracle, ws_variant):
     # the whole step (prefix, forward, backward) allocates nothing and clears nothing with memsets, so it
     # can be captured in a HIP graph; every replay must give the eager run's bits, also with other work
     # and synchronizations between the replays
@@ -570,7 +570,7 @@ def test_step_under_graph_capture_replays_bit_exactly(g, oracle):
     c = torch.empty_like(alpha)
     O, L = torch.empty_like(ins["Q"]), torch.empty_like(alpha)
     dQ, dK, dV, dal = torch.empty_like(ins["Q"]), torch.empty_like(ins["K"]), torch.empty_like(ins["V"]), torch.empty_like(alpha)
-    ws = torch.empty(g.gfwa_backward_workspace_bytes(torch.bfloat16, B, H, N, d, wl.w), dtype=torch.uint8, device=DEV)
+    ws = bwd_workspace(g, ins["Q"], wl.w)
 
     def step():
         g.gfwa_gate_prefix(alpha, c)
