@@ -113,8 +113,9 @@ def decode_only(args, g, torch) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # defaults long enough for the clocks to settle: the first ~30 steps after an idle period run up to 30 % slower
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="long_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--from-preactivation", action="store_true",
