@@ -14,6 +14,8 @@
 //                  S^T[k][q] = K (A, LDS) x Q^T (B, regs)   dP^T[k][q] = V (A, LDS) x dO^T (B, regs) - D
 //                  dQ^T[dd][q] += K^T (A, LDS transposing read) x dS^T (B = accumulator registers)
 //                plus the row sums of dS.
+//   3b. (d = 128, when the caller's workspace has room) dq from the dS blocks that launch 2 then stores: one
+//                matrix product instead of three, see "dS spill" below
 //   4. reverse scan of (column sums - row sums) -> dalpha   (gate_scan.hip)
 // In both kernels the row- (dkv) or key- (dq) dependent part of the exponent rides in the MFMA
 // accumulator (it is initialised from an LDS vector before the product), the lane-constant part is
@@ -280,10 +282,10 @@ __host__ __device__ inline int ds_spill_slots(int w, int nqb) {
 }
 constexpr int kSpillBlockBytes = 2048;
 
-// 8-wave variant (d = 128): two waves per SIMD.  The workgroup still owns 128 keys, but the waves kg
-// and kg + 4, which share a SIMD, both work on key group kg and take one of the two 32-query blocks
-// of every tile each, so that one wave's MFMAs run while the other does its softmax arithmetic or
-// waits for LDS.  Two waves per SIMD leave 256 registers per wave: the dK, dV accumulators (128) and
+// 8-wave variant (d = 128): two waves per SIMD.  The workgroup still owns 128 keys, but two waves work
+// on every key group and take one of the two 32-query blocks of every tile each, so that on every SIMD
+// one wave's MFMAs run while the other does its softmax arithmetic or waits for LDS.  Two waves per
+// SIMD leave 256 registers per wave: the dK, dV accumulators (128) and
 // S, dP (32) stay, the K and V fragments do not - the 128 keys of K and V are staged in LDS once per
 // workgroup and read as B operands like the Q and dO tiles are read as A operands.  At the end the
 // two waves of a key group add their accumulators through LDS.
