@@ -500,6 +500,8 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                     // Q and dO tiles the neighbouring workgroups are about to re-read out of the L2
                     __builtin_nontemporal_store(dsf[0], reinterpret_cast<bf16x8*>(blk + spill_lane0));
                     __builtin_nontemporal_store(dsf[1], reinterpret_cast<bf16x8*>(blk + spill_lane1));
+                    // the wait at the end of the tile counts on these two being issued by then
+                    asm volatile("" ::: "memory");
                 }
                 if (D != 128) {
 #pragma unroll
