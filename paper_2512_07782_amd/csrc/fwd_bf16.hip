@@ -199,6 +199,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     f32x16 s[2];     // S^T of the two blocks of the current tile (0: upper 32 keys, 1: lower)
     u32x4 pf[2][2];  // their probabilities as B operands (bf16 pairs)
     bool pending;    // the previous tile left a P that still has to be multiplied into O
+    bool fresh;      // no tile of the current query tile has set this wave's reference exponent yet
+    constexpr bool kFirstTileShortcut = D == 64;
     constexpr float kBig = 1.152921504606846976e18f;  // 2^60
 
     // one key tile; the ring slot is a compile-time constant so that every LDS address is a
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                     }
                 }
             }
-            float tsum;
+            float tsum = 0.f;
             auto exponentiate = [&]() __attribute__((always_inline)) {
                 const float nm = -m * sl;
                 float part[4] = {0.f, 0.f, 0.f, 0.f};
@@ -302,8 +304,11 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                 }
                 tsum = (part[0] + part[1]) + (part[2] + part[3]);
             };
-            exponentiate();
-            if (__builtin_amdgcn_ballot_w64(!(tsum <= kBig)) != 0) {
+            // d = 64 (short bands, the first tile weighs more): a wave's first tile, whose reference exponent is
+            // still the initial one, goes straight to the slow path instead of trying the fast one first
+            const bool first = kFirstTileShortcut && fresh;
+            if (!first) exponentiate();
+            if (first || __builtin_amdgcn_ballot_w64(!(tsum <= kBig)) != 0) {
                 // slow path: true maximum of the tile, common to the two halves of the wave
                 float mx = -INFINITY;
 #pragma unroll
@@ -317,13 +322,16 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
                 const float a = fast_exp2((m - mnew) * sl);
                 m = mnew;
                 l *= a;
+                if (!first) {  // (O is still zero on a first tile)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                    for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) o[db][v] *= a;
+                        for (int v = 0; v < 16; ++v) o[db][v] *= a;
+                }
                 exponentiate();
             }
             l += tsum;
+            fresh = false;
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
@@ -347,6 +355,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 #pragma unroll
     for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
     pending = false;
+    fresh = true;
     // T = ntiles is the drain step (only the PV product of the last tile)
     for (int T = 0; T <= ntiles; T += 4) {
         tile_step(std::integral_constant<int, 0>{}, T);
