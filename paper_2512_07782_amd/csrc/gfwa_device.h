@@ -105,32 +105,38 @@ __device__ __forceinline__ bf16x8 lds_read_frag(const char* tile, int r0, int kc
 
 
 // Direct global->LDS loads: every active lane p fetches 16 (4) bytes from  sbase + voff  and the
-// data lands at lds_base + 16*p (4*p); lds_base is wave-uniform and travels in M0 (declared clobbered, so
-// the compiler keeps nothing of its own there across a load).  Issued through inline assembly
+// data lands at lds_base + 16*p (4*p); lds_base is wave-uniform and travels in M0, which is saved
+// and restored because the compiler may keep its own value there.  Issued through inline assembly
 // on purpose: their completion is tracked by hand with vmcnt waits in front of the workgroup
 // barrier, whereas loads the compiler knows about make it wait for all of them before every LDS
 // read, which undoes any prefetch.
 __device__ __forceinline__ void dma16(const void* sbase, unsigned voff, const void* lds_base) {
     const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;  // LDS pointers are 32-bit offsets
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+    unsigned saved;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(sbase)
+        : "memory");
 }
 // the same for data that is read once (non-temporal: first in line for eviction from the caches)
 __device__ __forceinline__ void dma16_stream(const void* sbase, unsigned voff, const void* lds_base) {
     const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+    unsigned saved;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt\n\ts_mov_b32 m0, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(sbase)
+        : "memory");
 }
 __device__ __forceinline__ void dma4(const void* sbase, unsigned voff, const void* lds_base) {
     const unsigned lds_addr = (unsigned)(uintptr_t)lds_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+    unsigned saved;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b32 m0, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(sbase)
+        : "memory");
 }
 // s_waitcnt that waits only for vmcnt <= n (gfx9 encoding: expcnt and lgkmcnt fields left at max)
 constexpr int vmcnt_only(int n) { return 0x0f70 | (n & 0xf) | ((n >> 4) << 14); }
