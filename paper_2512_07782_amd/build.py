@@ -54,8 +54,8 @@ def _drain(procs, verbose):
         out = "\n".join(l for l in out.splitlines() if "not a recognized feature" not in l)
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
-        if verbose and out.strip():
-            print(out)
+        if out.strip() and (verbose or "warning:" in out):  # warnings are always shown
+            print(out, flush=True)
 
 
 if __name__ == "__main__":

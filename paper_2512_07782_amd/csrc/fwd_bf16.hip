@@ -176,7 +176,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         gaddr = base + offsetof(FwdSmem<D>, g) + 16 * h;
     }
     constexpr int kTileBytes = kTileRows * D * 2;
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
     auto read_k = [&](int kc, int disp) -> bf16x8 {
         return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(kaddr[kc] + disp);
     };
