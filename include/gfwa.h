@@ -5,8 +5,9 @@
  * Conventions shared by every entry point
  * ---------------------------------------
  *  - All data pointers are DEVICE pointers owned by the caller.  The library allocates no
- *    persistent device memory and never frees anything.  Inputs are never written; outputs
- *    are fully overwritten (no accumulate-into semantics).
+ *    device memory and never frees anything (the one fixed-size array gfwa_decode_static works
+ *    in is part of the library's code object).  Inputs are never written; outputs are fully
+ *    overwritten (no accumulate-into semantics).
  *  - Dense row-major layouts: Q, K, V, O, dO, dQ, dK, dV are [B, H, N, d] with d fastest;
  *    alpha, c, L, dalpha are [B, H, N] with N fastest.  Matrix pointers must be 16-byte
  *    aligned, vector pointers 4-byte aligned.
@@ -39,7 +40,9 @@ typedef enum {
     GFWA_ERR_DIM = -2,         /* B, H, N or d <= 0, w < 1, or B*H*N*d exceeds the index range */
     GFWA_ERR_UNSUPPORTED = -3, /* d not in {64, 128} or unknown dtype */
     GFWA_ERR_ALIGN = -4,       /* pointer alignment */
-    GFWA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than gfwa_backward_workspace_bytes() */
+    GFWA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than the matching gfwa_*_workspace_bytes() call
+                                  (backward, decode, scan-then-propagate) asks for; gfwa_decode_static:
+                                  the sizes need more than the library's own scratch holds */
     GFWA_ERR_HIP = -6          /* the HIP runtime refused a launch; see gfwa_strerror */
 } gfwa_status_t;
 
@@ -178,6 +181,20 @@ int gfwa_decode(gfwa_dtype_t dt, const void *q, const void *Kc, const void *Vc, 
                 const float *alpha_t, const int *pos, void *o, float *L, void *workspace,
                 size_t workspace_bytes, int B, int H, int Hkv, int T, int d, int w, float scale,
                 gfwa_stream_t stream);
+
+/*
+ * gfwa_decode for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as gfwa_decode, but the per-chunk partial results live in a 32 MiB array inside the
+ * library's code object (one copy per GPU, held until the process ends); the call allocates and
+ * frees nothing.  Sizes with gfwa_decode_workspace_bytes(B, H, T, d, w) > 33554432 are rejected with
+ * GFWA_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share that array: two calls that
+ * may run at the same time on one GPU (different streams) race and must be serialised by the caller;
+ * calls on one stream are ordered and safe.  Nothing in the array has to start at zero.
+ */
+int gfwa_decode_static(gfwa_dtype_t dt, const void *q, const void *Kc, const void *Vc, float *c,
+                       const float *alpha_t, const int *pos, void *o, float *L, int B, int H, int Hkv,
+                       int T, int d, int w, float scale, gfwa_stream_t stream);
 
 /* Static, human-readable text for a status code (for GFWA_ERR_HIP: the last HIP error text). */
 const char *gfwa_strerror(int code);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     gfwa_backward_fast_workspace_bytes,
     gfwa_backward_workspace_bytes,
     gfwa_decode,
+    gfwa_decode_static,
     gfwa_decode_workspace_bytes,
     gfwa_forward,
     gfwa_forward_gqa,

@@ -19,7 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 GFWA_BF16, GFWA_F32 = 0, 1
 
 EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_backward",
-           "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes", "gfwa_gate_prefix_stp",
+           "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_decode_static", "gfwa_gate_scan_workspace_bytes", "gfwa_gate_prefix_stp",
            "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
 N_KERNELS = 12
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_decode.argtypes = [i, vp, vp, vp, fp, fp, vp, vp, fp, vp, ctypes.c_size_t, i, i, i, i, i, i, f, vp]
     lib.gfwa_decode.restype = i
+    lib.gfwa_decode_static.argtypes = [i, vp, vp, vp, fp, fp, vp, vp, fp, i, i, i, i, i, i, f, vp]
+    lib.gfwa_decode_static.restype = i
     lib.gfwa_gate_scan_workspace_bytes.argtypes = [i, i, i]
     lib.gfwa_gate_scan_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_gate_prefix_stp.argtypes = [fp, fp, f, fp, vp, ctypes.c_size_t, i, i, i, vp]
@@ -373,6 +375,34 @@ def gfwa_decode(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: torch.Te
                                       o.data_ptr(), L.data_ptr(), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), B, H, Hkv, T, d, int(w),
                                       float(scale), _stream()))
+    return o, L
+
+
+def gfwa_decode_static(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: torch.Tensor, pos: torch.Tensor,
+                       w: int, scale: float, o: torch.Tensor, L: torch.Tensor,
+                       alpha_t: Optional[torch.Tensor] = None):
+    """gfwa_decode without a workspace and without any allocation: the caller passes the outputs
+    o [B,H,d] and L [B,H]; the partial results live in the library's own scratch."""
+    if q.dim() != 3 or Kc.dim() != 4:
+        raise ValueError("q must be [B,H,d] and Kc [B,Hkv,T,d]")
+    B, H, d = q.shape
+    Hkv, T = Kc.shape[1], Kc.shape[2]
+    if Hkv <= 0 or H % Hkv != 0:
+        raise ValueError(f"the number of key/value heads ({Hkv}) must divide the number of query heads ({H})")
+    dt = _dt(q)
+    _need(q, (B, H, d), q.dtype, "q")
+    for name, t in (("Kc", Kc), ("Vc", Vc)):
+        _need(t, (B, Hkv, T, d), q.dtype, name)
+    _need(c, (B, H, T), torch.float32, "c")
+    _need(pos, (B,), torch.int32, "pos")
+    if alpha_t is not None:
+        _need(alpha_t, (B, H), torch.float32, "alpha_t")
+    _need(o, (B, H, d), q.dtype, "o")
+    _need(L, (B, H), torch.float32, "L")
+    _check(load_library().gfwa_decode_static(dt, q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), c.data_ptr(),
+                                             alpha_t.data_ptr() if alpha_t is not None else None, pos.data_ptr(),
+                                             o.data_ptr(), L.data_ptr(), B, H, Hkv, T, d, int(w), float(scale),
+                                             _stream()))
     return o, L
 
 

@@ -218,6 +218,23 @@ int gfwa_decode(gfwa_dtype_t dt, const void* q, const void* Kc, const void* Vc, 
                              w, scale, stream));
 }
 
+int gfwa_decode_static(gfwa_dtype_t dt, const void* q, const void* Kc, const void* Vc, float* c,
+                       const float* alpha_t, const int* pos, void* o, float* L, int B, int H, int Hkv, int T, int d,
+                       int w, float scale, gfwa_stream_t stream) {
+    if (!q || !Kc || !Vc || !c || !pos || !o) return GFWA_ERR_NULL;
+    if (int r = check_dims(B, H, T, d, w, true)) return r;
+    if (Hkv <= 0 || H % Hkv != 0) return GFWA_ERR_DIM;
+    if (dt != GFWA_BF16 && dt != GFWA_F32) return GFWA_ERR_UNSUPPORTED;
+    if (!aligned(q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(o, 16) || !aligned(c, 4) ||
+        !aligned(pos, 4) || (alpha_t && !aligned(alpha_t, 4)) || (L && !aligned(L, 4)))
+        return GFWA_ERR_ALIGN;
+    if (gfwa_decode_workspace_bytes(B, H, T, d, w) > kDecodeStaticBytes) return GFWA_ERR_WORKSPACE;
+    float* part = nullptr;
+    if (hipError_t e = decode_static_scratch(&part)) return hip_status(e);
+    return hip_status(decode(dt == GFWA_BF16, q, Kc, Vc, c, alpha_t, pos, o, L, part, B, H, Hkv, T, d, w, scale,
+                             stream));
+}
+
 const char* gfwa_strerror(int code) {
     switch (code) {
         case GFWA_OK: return "ok";
@@ -225,7 +242,9 @@ const char* gfwa_strerror(int code) {
         case GFWA_ERR_DIM: return "invalid size: B, H, N, d must be > 0, w >= 1, Hkv > 0 dividing H, within index range";
         case GFWA_ERR_UNSUPPORTED: return "unsupported head dimension (64 or 128) or dtype";
         case GFWA_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes matrices, 4 bytes vectors)";
-        case GFWA_ERR_WORKSPACE: return "workspace missing or smaller than gfwa_backward_workspace_bytes() / gfwa_decode_workspace_bytes()";
+        case GFWA_ERR_WORKSPACE:
+            return "workspace missing or smaller than the matching gfwa_*_workspace_bytes() call asks for; for "
+                   "gfwa_decode_static: the sizes need more than the library's 32 MiB of scratch";
         case GFWA_ERR_HIP: return g_hip_msg;
         default: return "unknown status code";
     }

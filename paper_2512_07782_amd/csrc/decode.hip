@@ -380,6 +380,26 @@ static hipError_t launch_decode(const T* q, const T* Kc, const T* Vc, float* c, 
     return hipGetLastError();
 }
 
+// Scratch of the allocation-free entry point: one array per GPU, held from the moment the code object
+// is loaded until the process ends.  The name `scratch` is only a host-side handle of the symbol; the
+// address a kernel may use is asked for once per device and kept.
+static __device__ __align__(256) float scratch[kDecodeStaticBytes / sizeof(float)];
+
+hipError_t decode_static_scratch(float** ptr) {
+    static float* per_device[64];  // nullptr: not asked for yet
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    float* p = __atomic_load_n(&per_device[dev], __ATOMIC_ACQUIRE);
+    if (p == nullptr) {
+        if (hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch))) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        __atomic_store_n(&per_device[dev], p, __ATOMIC_RELEASE);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
 hipError_t decode(bool bf16, const void* q, const void* Kc, const void* Vc, float* c, const float* alpha_t,
                   const int* pos, void* o, float* L, float* part, int B, int H, int Hkv, int Tlen, int d, int w,
                   float scale, hipStream_t s) {

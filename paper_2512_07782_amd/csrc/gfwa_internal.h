@@ -45,6 +45,11 @@ hipError_t decode(bool bf16, const void* q, const void* Kc, const void* Vc, floa
                   const int* pos, void* o, float* L, float* part, int B, int H, int Hkv, int Tlen, int d, int w,
                   float scale, hipStream_t s);
 
+// Device address, on the current device, of the library's own decode scratch of kDecodeStaticBytes
+// (looked up on the first call per device, no allocation).
+constexpr size_t kDecodeStaticBytes = (size_t)32 << 20;
+hipError_t decode_static_scratch(float** ptr);
+
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
 enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,
                 kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernScanSegmentSum,

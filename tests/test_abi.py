@@ -24,7 +24,7 @@ def declared_functions():
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
-                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_gate_scan_workspace_bytes",
+                            "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_decode_static", "gfwa_gate_scan_workspace_bytes",
                             "gfwa_gate_prefix_stp",
                             "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
@@ -86,6 +86,15 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_decode(*dec(wsb=16)) == -5
     assert lib.gfwa_decode_workspace_bytes(2, 4, 1000, 128, 300) == (2 * 4 * 2 * 130 * 4 + 255) // 256 * 256   # two chunks of 256 keys
     assert lib.gfwa_decode_workspace_bytes(2, 4, 1000, 96, 300) == 0
+    # the same step on the library's own scratch: argument checks, and sizes beyond its 32 MiB are refused
+    decs = lambda **kw: [0, kw.get("q", good), good, good, good, None, good, good, None, kw.get("B", 1), 4,
+                         kw.get("Hkv", 2), kw.get("T", 64), kw.get("d", 128), kw.get("w", 16), f, None]
+    assert lib.gfwa_decode_static(*decs(q=None)) == -1
+    assert lib.gfwa_decode_static(*decs(Hkv=3)) == -2
+    assert lib.gfwa_decode_static(*decs(d=96)) == -3
+    assert lib.gfwa_decode_static(*decs(q=odd)) == -4
+    assert lib.gfwa_decode_workspace_bytes(4096, 4, 8192, 128, 8192) > 32 << 20
+    assert lib.gfwa_decode_static(*decs(B=4096, T=8192, w=8192)) == -5
     # forward
     args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
                          kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]
