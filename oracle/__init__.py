@@ -49,12 +49,14 @@ def _load() -> ctypes.CDLL:
         lib.gfwa_oracle_forward.argtypes = [_dp, _dp, _dp, _dp, L, L, L, D, _dp, _dp, _dp]
         lib.gfwa_oracle_backward_c.argtypes = [_dp, _dp, _dp, _dp, _dp, L, L, L, D,
                                                _dp, _dp, _dp, _dp, _dp]
+        lib.gfwa_oracle_backward_saved_O.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, L, L, L, D,
+                                                     _dp, _dp, _dp, _dp, _dp]
         lib.gfwa_oracle_dalpha_from_dc.argtypes = [_dp, _dp, L]
         lib.gfwa_oracle_dalpha_direct.argtypes = [_dp, _dp, L, L]
         lib.gfwa_oracle_gate_activation.argtypes = [_dp, _dp, D, _dp, L]
         lib.gfwa_oracle_gate_activation_backward.argtypes = [_dp, _dp, D, _dp, _dp, _dp, L]
         for f in ("gfwa_oracle_prefix", "gfwa_oracle_forward_c", "gfwa_oracle_forward",
-                  "gfwa_oracle_backward_c", "gfwa_oracle_dalpha_from_dc",
+                  "gfwa_oracle_backward_c", "gfwa_oracle_backward_saved_O", "gfwa_oracle_dalpha_from_dc",
                   "gfwa_oracle_dalpha_direct", "gfwa_oracle_gate_activation",
                   "gfwa_oracle_gate_activation_backward"):
             getattr(lib, f).restype = None
@@ -146,10 +148,15 @@ def forward(Q, K, V, alpha, w: int, scale: float):
 # --------------------------------------------------------------------------
 # backward (App. E.2, Alg. 3)
 # --------------------------------------------------------------------------
-def backward_from_c(Q, K, V, c, dO, w: int, scale: float, return_dS: bool = False) -> Dict[str, np.ndarray]:
-    """dQ, dK, dV, dc (gradient w.r.t. the prefix) and dalpha (reverse inclusive scan of dc)."""
+def backward_from_c(Q, K, V, c, dO, w: int, scale: float, return_dS: bool = False,
+                    O_saved=None) -> Dict[str, np.ndarray]:
+    """dQ, dK, dV, dc (gradient w.r.t. the prefix) and dalpha (reverse inclusive scan of dc).
+    With O_saved [.., N, d]: Alg. 3 evaluated on that saved forward output (D = rowsum(dO * O_saved))
+    instead of on the exact output - what the algorithm returns when O was rounded for storage."""
     lib = _load()
     Qf, Kf, Vf, dOf = (_flat_heads(x, 2) for x in (Q, K, V, dO))
+    Of = None if O_saved is None else _flat_heads(O_saved, 2)
+    assert Of is None or Of.shape == Qf.shape
     cf = _flat_heads(c, 1)
     BH, N, d = Qf.shape
     wb = min(int(w), N)
@@ -158,9 +165,14 @@ def backward_from_c(Q, K, V, c, dO, w: int, scale: float, return_dS: bool = Fals
     dalpha = np.empty((BH, N), dtype=np.float64)
     dS = np.empty((BH, N, wb), dtype=np.float64) if return_dS else None
     for r in range(BH):
-        lib.gfwa_oracle_backward_c(_p(Qf[r]), _p(Kf[r]), _p(Vf[r]), _p(cf[r]), _p(dOf[r]), N, d,
-                                   int(w), float(scale), _p(dQ[r]), _p(dK[r]), _p(dV[r]),
-                                   _p(dc[r]), _p(dS[r]) if return_dS else None)
+        if Of is None:
+            lib.gfwa_oracle_backward_c(_p(Qf[r]), _p(Kf[r]), _p(Vf[r]), _p(cf[r]), _p(dOf[r]), N, d,
+                                       int(w), float(scale), _p(dQ[r]), _p(dK[r]), _p(dV[r]),
+                                       _p(dc[r]), _p(dS[r]) if return_dS else None)
+        else:
+            lib.gfwa_oracle_backward_saved_O(_p(Qf[r]), _p(Kf[r]), _p(Vf[r]), _p(cf[r]), _p(dOf[r]), _p(Of[r]),
+                                             N, d, int(w), float(scale), _p(dQ[r]), _p(dK[r]), _p(dV[r]),
+                                             _p(dc[r]), _p(dS[r]) if return_dS else None)
         lib.gfwa_oracle_dalpha_from_dc(_p(dc[r]), _p(dalpha[r]), N)
     shp, vshp = np.shape(Q), np.shape(c)
     out = {"dQ": dQ.reshape(shp), "dK": dK.reshape(shp), "dV": dV.reshape(shp),
@@ -194,11 +206,11 @@ def forward_gqa_from_c(Q, K, V, c, w: int, scale: float):
     return forward_from_c(Q, _repeat_kv(K, H), _repeat_kv(V, H), c, w, scale)
 
 
-def backward_gqa_from_c(Q, K, V, c, dO, w: int, scale: float) -> Dict[str, np.ndarray]:
+def backward_gqa_from_c(Q, K, V, c, dO, w: int, scale: float, O_saved=None) -> Dict[str, np.ndarray]:
     """dQ [B,H,N,d], dK, dV [B,Hkv,N,d], dc, dalpha [B,H,N]."""
     B, H, N, d = np.shape(Q)
     Hkv = np.shape(K)[1]
-    out = backward_from_c(Q, _repeat_kv(K, H), _repeat_kv(V, H), c, dO, w, scale)
+    out = backward_from_c(Q, _repeat_kv(K, H), _repeat_kv(V, H), c, dO, w, scale, O_saved=O_saved)
     for k in ("dK", "dV"):
         out[k] = out[k].reshape(B, Hkv, H // Hkv, N, d).sum(axis=2)
     return out

@@ -137,9 +137,10 @@ void gfwa_oracle_forward(const double *Q, const double *K, const double *V, cons
  * into the gradient w.r.t. alpha.  dS_band (optional, [N, min(w,N)]) returns the band of
  * dS for the independent d(alpha) formula.
  */
-void gfwa_oracle_backward_c(const double *Q, const double *K, const double *V, const double *c,
-                            const double *dO, long N, long d, long w, double scale, double *dQ,
-                            double *dK, double *dV, double *dc, double *dS_band_out) {
+static void backward_one_head(const double *Q, const double *K, const double *V, const double *c,
+                              const double *dO, const double *O_saved, long N, long d, long w,
+                              double scale, double *dQ, double *dK, double *dV, double *dc,
+                              double *dS_band_out) {
     long wb = w < N ? w : N;
     size_t band = (size_t)N * (size_t)wb;
     double *O = (double *)malloc(sizeof(double) * (size_t)N * (size_t)d);
@@ -149,6 +150,7 @@ void gfwa_oracle_backward_c(const double *Q, const double *K, const double *V, c
     double *rowsum = (double *)malloc(sizeof(double) * (size_t)N);
 
     gfwa_oracle_forward_c(Q, K, V, c, N, d, w, scale, O, L, P);
+    const double *Ouse = O_saved ? O_saved : O; /* the output that enters D */
 
     /* pass over query rows: D, dP, dS, dQ, row sums */
 #pragma omp parallel for schedule(dynamic, 16)
@@ -156,7 +158,7 @@ void gfwa_oracle_backward_c(const double *Q, const double *K, const double *V, c
         long lo = window_lo(t, w);
         long n = t - lo + 1;
         double D = 0.0;
-        for (long x = 0; x < d; ++x) D += dO[t * d + x] * O[t * d + x];
+        for (long x = 0; x < d; ++x) D += dO[t * d + x] * Ouse[t * d + x];
         double rs = 0.0;
         for (long x = 0; x < d; ++x) dQ[t * d + x] = 0.0;
         for (long j = 0; j < wb; ++j) dS[t * wb + j] = 0.0;
@@ -200,6 +202,27 @@ void gfwa_oracle_backward_c(const double *Q, const double *K, const double *V, c
     free(P);
     if (!dS_band_out) free(dS);
     free(rowsum);
+}
+
+void gfwa_oracle_backward_c(const double *Q, const double *K, const double *V, const double *c,
+                            const double *dO, long N, long d, long w, double scale, double *dQ,
+                            double *dK, double *dV, double *dc, double *dS_band_out) {
+    backward_one_head(Q, K, V, c, dO, NULL, N, d, w, scale, dQ, dK, dV, dc, dS_band_out);
+}
+
+/*
+ * The same formulas with D_t = <dO_t, O_saved_t> taken on a GIVEN output O_saved [N, d] instead of
+ * the output recomputed here.  App. E.2 / Alg. 3 is stated this way: the saved forward output O is
+ * an input of the backward and D = rowsum(dO * O) is formed from it.  With O_saved equal to the
+ * exact output this is the gradient; with an output that was rounded for storage it is what the
+ * algorithm returns on that input, and differs from the gradient by  -P_ti * (D_saved - D)_t  in
+ * every dS_ti.  P is still the exact softmax (the logsumexp is recomputed, not taken from outside).
+ */
+void gfwa_oracle_backward_saved_O(const double *Q, const double *K, const double *V, const double *c,
+                                  const double *dO, const double *O_saved, long N, long d, long w,
+                                  double scale, double *dQ, double *dK, double *dV, double *dc,
+                                  double *dS_band_out) {
+    backward_one_head(Q, K, V, c, dO, O_saved, N, d, w, scale, dQ, dK, dV, dc, dS_band_out);
 }
 
 /* c_p = sum_{q<=p} alpha_q, so d(alpha_q) = sum_{p>=q} dc_p  (reverse inclusive scan;

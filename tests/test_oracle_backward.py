@@ -136,3 +136,63 @@ def test_batched_backward_shapes(oracle):
     g01 = oracle.backward(Q[0, 1], K[0, 1], V[0, 1], alpha[0, 1], dO[0, 1], w, 0.5)
     np.testing.assert_allclose(g["dK"][0, 1], g01["dK"], rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(g["dalpha"][0, 1], g01["dalpha"], rtol=1e-13, atol=1e-15)
+
+
+# ---- Alg. 3 evaluated on a given (e.g. storage-rounded) forward output -----------------------------
+def band_to_dense(Pb, N, w):
+    P = np.zeros((N, N))
+    for t in range(N):
+        lo = max(0, t - w + 1)
+        P[t, lo:t + 1] = Pb[t, :t - lo + 1]
+    return P
+
+
+@pytest.mark.parametrize("N,d,w", [(2, 8, 2), (2, 4, 9), (23, 6, 5), (30, 3, 64)])
+def test_P19_saved_output_variant(oracle, N, d, w):
+    """backward_from_c(O_saved=...) (App. E.2, Alg. 3: D = rowsum(dO * O) on the saved O).
+    (a) on the exact output it is the gradient, bit for bit;
+    (b) on a perturbed output the difference to the gradient is the closed form that follows from
+        dS_ti = P_ti (dP_ti - D_t):  with e_t = <dO_t, O_saved_t - O_t>,
+        dQ -= scale * diag(e) P K,  dK -= scale * (diag(e) P)^T Q,  dV unchanged,
+        dc_p -= sum_t e_t P_tp - e_p   (written here with dense numpy matrices);
+    (c) the row sums of dS then equal -e_t instead of 0, and sum_p dc_p stays 0."""
+    Q, K, V, alpha, dO = rand_case(N, d, np.random.default_rng(100 * N + w))
+    scale = 0.37
+    c = oracle.gate_prefix(alpha)
+    O, _, Pb = oracle.forward_from_c(Q, K, V, c, w, scale, return_P=True)
+    g = oracle.backward_from_c(Q, K, V, c, dO, w, scale, return_dS=True)
+    g0 = oracle.backward_from_c(Q, K, V, c, dO, w, scale, return_dS=True, O_saved=O)
+    for k in g:
+        np.testing.assert_array_equal(g[k], g0[k])
+    Os = O + 0.01 * np.random.default_rng(5).standard_normal(O.shape)
+    gs = oracle.backward_from_c(Q, K, V, c, dO, w, scale, return_dS=True, O_saved=Os)
+    P = band_to_dense(Pb, N, w)
+    e = ((Os - O) * dO).sum(axis=1)
+    eP = e[:, None] * P
+    np.testing.assert_allclose(gs["dQ"], g["dQ"] - scale * eP @ K, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gs["dK"], g["dK"] - scale * eP.T @ Q, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(gs["dV"], g["dV"])
+    np.testing.assert_allclose(gs["dc"], g["dc"] - (eP.sum(axis=0) - e), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gs["dS"].sum(axis=-1), -e, rtol=0, atol=1e-12)
+    assert abs(gs["dc"].sum()) <= 1e-12
+    assert abs(gs["dalpha"][0]) <= 1e-12
+    # and the telescoped form of d(alpha) holds for this dS as for any other
+    np.testing.assert_allclose(oracle.dalpha_direct(gs["dS"], w), gs["dalpha"], rtol=0, atol=1e-12)
+
+
+def test_P19_rounded_output_explains_tiny_sequence_errors(oracle):
+    """Storing O in bf16 perturbs D_t by up to 2^-9 sum_x |dO_tx O_tx|; when a whole gradient tensor
+    rests on one or two dS entries (N = 2: dS_10 = -dS_11 is the only non-zero pair) nothing averages
+    that out, and Alg. 3 on the stored output is about one per cent away from the gradient."""
+    import gfwa_inputs as gi
+    wl = gi.custom("fz", 1, 1, 2, 64, 2, "bf16", alpha_mu=0.5, index=31, backward=True)
+    ins = {t: gi.make_tensor(wl, t)[0, 0] for t in ("Q", "K", "V", "alpha", "dO")}
+    c = oracle.gate_prefix(ins["alpha"])
+    O, _ = oracle.forward_from_c(ins["Q"], ins["K"], ins["V"], c, wl.w, wl.scale)
+    g = oracle.backward_from_c(ins["Q"], ins["K"], ins["V"], c, ins["dO"], wl.w, wl.scale)
+    gs = oracle.backward_from_c(ins["Q"], ins["K"], ins["V"], c, ins["dO"], wl.w, wl.scale,
+                                O_saved=gi.round_to_bf16(O))
+    r = np.linalg.norm(gs["dQ"] - g["dQ"]) / np.linalg.norm(g["dQ"])
+    assert 5e-3 <= r <= 2e-2, r
+    bound = 2.0 ** -9 * np.abs(ins["dO"] * O).sum(axis=1)          # |D_saved - D| per row, worst case
+    assert (np.abs(((gi.round_to_bf16(O) - O) * ins["dO"]).sum(axis=1)) <= bound).all()
