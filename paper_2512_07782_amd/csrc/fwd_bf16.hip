@@ -1,43 +1,42 @@
 // GatedFWA fused forward for bf16 storage on gfx950 (paper Alg. 2, re-designed for CDNA4).
 //
-// One workgroup of 8 waves per CU owns a tile of 256 consecutive queries of one (b,h); a wave owns
-// 32 of them.  Key/value tiles of 64 keys travel global -> LDS by direct loads (no staging
-// registers, no LDS stores) through a ring of kRing buffers, and only the tiles that intersect the
-// band [q0-w+1, q0+255] are visited; inside a tile every wave skips the 32-key blocks that lie
-// wholly outside the band of its own queries, and masks only the blocks the band edge or the
-// diagonal cuts.
+// One workgroup of 4 waves per CU (one wave per SIMD, with the whole register file of its SIMD) owns a
+// tile of 256 consecutive queries of one (b,h); a wave owns 64 of them as two 32-query blocks.  Key/value
+// tiles of 64 keys travel global -> LDS by direct loads (no staging registers, no LDS stores) through a
+// ring of kRing buffers, and only the tiles that intersect the band [q0-w+1, q0+255] are visited; inside
+// a tile every wave skips the 32-key blocks that lie wholly outside the band of its own queries, and
+// masks only the blocks the band edge or the diagonal cuts.
 //
-// The products are formed transposed so that a lane owns one query:
+// The products are formed transposed so that a lane owns one query of each of its two blocks:
 //   S^T[key][query]  = g[key] + K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
 //   O^T[dd][query]  += V_tile^T (A operand, LDS transposing read)  x  P^T (B operand = the S^T
 //                      accumulator registers converted to bf16 in place)
 // so the row max / row sum of the online softmax are in-lane plus one exchange between the two
-// halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.
+// halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.  Every K
+// and V fragment read from LDS feeds two MFMAs (one per query block).
 //
-// Two-phase schedule.  The work of a wave on key tile T (two 32-key blocks) is split into a
-// matrix phase
-//   M(T):  S_T = g + K_T Q^T   and   O += V_{T-1}^T P_{T-1}        (32 MFMAs at d = 128)
-// and a vector phase
-//   X(T):  P_T = exp2(S_T * sl - m * sl), row sums                 (no MFMA)
-// The two waves that share a SIMD belong to different groups (waves 0-3 and 4-7).  There is one
-// workgroup barrier per key tile; the first group takes it after X(T), the second after M(T), so
-// the second group's vector phase runs next to the first group's next matrix phase: on every SIMD
-// one wave issues MFMAs while the other does the softmax arithmetic, instead of all waves queueing
-// for the same unit.
+// Software pipeline inside the wave.  With blocks of 32 keys numbered n in visiting order, iteration n
+// issues, as one straight-line instruction stream,
+//   matrix pipe:  S(n) = g + K Q^T      and      O += V^T P(n-2)          (32 MFMAs at d = 128)
+//   vector unit:  P(n-1) = exp2(S(n-1) * sl - m * sl), row sums
+//   LDS:          the fragments of the MFMAs four steps ahead
+// Nothing in an iteration depends on anything else in it, so the MFMAs issue back to back while the
+// exponentials of the previous block and the fragment reads of the next MFMAs fill the issue slots
+// between them (an MFMA occupies the matrix pipe for 32 cycles; about five vector and two LDS
+// instructions fit beside it).  One workgroup barrier per key tile hands the ring slots over.
 //
 // The gate bias rides in the MFMA accumulator: S is initialised with g_i = (c_i - c_base) / scale
 // straight from LDS before the K Q^T chain, so S = q.k + g_i and the probability is one fused
 // multiply-add plus one exp2, sl = scale * log2(e).  The per-query term -(c_t - c_base) is
 // constant along a row, cancels in the softmax, and is applied only to L.  c_base = c at the first
-// query of the tile keeps the fp32 differences window-local.  The row sum is taken over the
-// bf16-rounded probabilities (one packed dot-product per pair), i.e. over exactly the values that
-// enter the PV product.
+// query of the tile keeps the fp32 differences window-local.  The row sum is taken in fp32 over the
+// unrounded probabilities with plain adds.
 //
-// Deferred running max.  exp2 is taken against the reference exponent m left by earlier tiles
-// without first looking for the tile's own maximum; fp32 and bf16 share their exponent range, so a
-// probability may grow to 2^60 with no loss of precision.  Only when a lane's tile sum exceeds that
-// (always on a wave's first tile, where m is still "minus infinity") does the wave take the slow
-// path: find the true maximum, raise m, rescale O and l, and redo the exponentials.  Tiles are
+// Deferred running max.  exp2 is taken against the reference exponent m left by earlier blocks
+// without first looking for the block's own maximum; fp32 and bf16 share their exponent range, so a
+// probability may grow to 2^60 with no loss of precision.  Only when a lane's block sum exceeds that
+// (always on a query block's first key block, where m is still "minus infinity") does the wave take the
+// slow path: find the true maximum, raise m, rescale O and l, and redo the exponentials.  Blocks are
 // visited from the diagonal backwards, where the gate bias is largest, so this is rare.
 #include <cstddef>
 #include <type_traits>
@@ -48,10 +47,11 @@
 
 namespace gfwa {
 
-constexpr int kFwdWaves = 8;
+constexpr int kFwdWaves = 4;
 constexpr int kFwdThreads = 64 * kFwdWaves;
-constexpr int kFwdBR = 32 * kFwdWaves;  // queries per workgroup
-constexpr int kRing = 4;                // K/V tile slots: read for PV, read for S, two in flight
+constexpr int kQB = 1;                           // 32-query blocks per wave
+constexpr int kFwdBR = 32 * kQB * kFwdWaves;     // queries per workgroup
+constexpr int kRing = 2;                         // K and V tile slots each: one being read, one in flight
 
 template <int D>
 using FwdSmem = KvRingSmem<D, kRing>;
@@ -65,17 +65,14 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     constexpr int KC = D / 16;  // MFMA k-chunks along the head dimension
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
     using Loader = TilePairLoader<D, kFwdWaves>;
-    constexpr int kBatch = Loader::kLoadsPerTilePair + 1;  // loads one wave issues per tile (K, V, c)
     extern __shared__ __align__(16) char smem_raw[];
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wv >> 2;  // waves wv and wv + 4 share a SIMD and run in opposite phases
     const int h = lane >> 5, lq = lane & 31;
     const float sl = scale_log2;
     const float inv_scale = kLog2e / scale_log2;
-    const int jfull = N / kTileRows;  // tiles below jfull have all 64 rows inside the sequence
 
     // Persistent workgroups: workgroup b takes the query tiles xcd_remap(b) + k * gridDim.x, so the
     // loads of the next tile are issued before the results of the current one are stored.
@@ -83,14 +80,14 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     // head do not always fall to the same workgroups)
     const int wg_slot = xcd_remap(blockIdx.x, gridDim.x);
     int wg_step = 0;
-    auto tile_of = [&](int k) { return k * (int)gridDim.x + (wg_slot + 37 * k) % (int)gridDim.x; };
+    auto tile_of = [&](int k) __attribute__((always_inline)) { return k * (int)gridDim.x + (wg_slot + 37 * k) % (int)gridDim.x; };
     int tile = tile_of(0);
-    int bh, q0, qw0, t, j_lo, j_hi, ntiles;
+    int bh, q0, qw0, t0, j_lo, j_hi, ntiles;
     size_t head_off;
     const char *Kh, *Vh;
     const float* ch;
-    float cbase, cq;
-    bf16x8 qf[KC];  // Q^T fragments (B operand), resident for the whole tile loop
+    float cbase, cq[kQB];
+    bf16x8 qf[kQB][KC];  // Q^T fragments (B operand), resident for the whole tile loop
     auto set_tile = [&](int tl) __attribute__((always_inline)) {
         bh = tl / num_qtiles;
         q0 = (tl % num_qtiles) * BR;
@@ -100,16 +97,16 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         Vh = reinterpret_cast<const char*>(V + kv_off);
         ch = c + (size_t)bh * N;
         cbase = ch[q0];
-        // the two waves of a SIMD take slabs 128 queries apart: in the first and last key tiles of the band, where
-        // only the upper or the lower half of the queries has keys, every SIMD then still has one wave at work
-        qw0 = q0 + 32 * (wv & 3) + 128 * grp;  // first query of this wave
-        t = qw0 + lq;
-        {  // rows past N read row N-1
-            const bf16_t* qp = Q + head_off + (size_t)min(t, N - 1) * D + 8 * h;
+        qw0 = q0 + 32 * kQB * wv;  // first query of this wave
+        t0 = qw0 + lq;             // this lane's query in block 0; block qb: t0 + 32 qb
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) qf[kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
+        for (int qb = 0; qb < kQB; ++qb) {  // rows past N read row N-1
+            const int t = min(t0 + 32 * qb, N - 1);
+            const bf16_t* qp = Q + head_off + (size_t)t * D + 8 * h;
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
+            cq[qb] = ch[t] - cbase;
         }
-        cq = ch[min(t, N - 1)] - cbase;
         // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
         const int k_lo = max(0, q0 - w + 1);
         const int k_hi = min(N, q0 + BR) - 1;
@@ -118,39 +115,56 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         ntiles = j_hi - j_lo + 1;
     };
     set_tile(tile);
+    // ring slots that were never loaded are read by the first and last iterations of a band (as operands
+    // of products with zero probabilities, or into scores that the mask overrides): make them finite once
+    for (int o16 = tid * 16; o16 < (int)(offsetof(FwdSmem<D>, craw)); o16 += kFwdThreads * 16)
+        *reinterpret_cast<f32x4*>(smem_raw + o16) = f32x4{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
 
-    Loader loader;
-    loader.init(wv, lane);
-    // every wave issues the same kBatch loads per tile, so the vmcnt bookkeeping is uniform; the
-    // 64 c values are fetched by all waves to the same place (identical data)
-    // Tiles are visited from the diagonal backwards: the gate bias only falls with distance, so
-    // the first blocks set the running max and later ones hardly ever force a rescale of O.
-    auto issue_tile = [&](int T) {  // T = position in visiting order, tile j_hi - T
-        const int j = j_hi - T, buf = T % kRing;
-        dma4(ch, (unsigned)min(j * kTileRows + lane, N - 1) * 4u, sm.craw[buf]);
-        loader.load(Kh, Vh, j, jfull, N, sm.k[buf], sm.v[buf]);
+    // Tile loads, 1 KB per wave instruction (kRowsPerLoad rows of a tile): wave wv fills rows
+    // kRowsPerWave wv .. of a tile with kLoadsPerWave loads.  Lane p of a load writes LDS row p / chunks-per-row
+    // of its group at physical chunk p % chunks-per-row and therefore fetches the logical chunk the swizzle
+    // maps there.  Rows at or beyond N read row N-1 (finite data that the band mask keeps out of every sum);
+    // a tile index below 0 reads tile 0 (the loads of the two steps after a band's last tile, which nothing reads).
+    constexpr int kRowsPerLoad = Loader::kRowsPerLoad, kLoadsPerWave = Loader::kLoadsPerWave;
+    constexpr int kRowsPerWave = Loader::kRowsPerWave, kChunksPerRow = Loader::kChunksPerRow;
+    static_assert(kRowsPerLoad == 4 || kRowsPerLoad == 8, "1 KB loads of 256- or 128-byte rows");
+    // load g fetches row ld_row0 + kRowsPerLoad g of the tile; the swizzle of that row differs from load 0's only
+    // in chunk bits that g alone sets (d = 128: bits 0-1 = (row >> 2) & 3 = g; d = 64: bit 0 = (row >> 3) & 1 = g & 1)
+    const int ld_row0 = kRowsPerWave * wv + lane / kChunksPerRow;
+    const unsigned ld_chunk0 = (unsigned)(swz_chunk<D>(ld_row0, lane % kChunksPerRow) * 16);
+    // load g of tile T (position in visiting order: tile j_hi - T) of the matrix at Mh into its ring slot
+    auto load_piece = [&](const char* Mh, char (&ring)[kRing][kTileRows * D * 2], int T, int g) __attribute__((always_inline)) {
+        const int j = max(j_hi - T, 0);
+        const int row = min(j * kTileRows + kRowsPerLoad * g + ld_row0, N - 1);
+        const unsigned chunk = ld_chunk0 ^ (unsigned)((swz_chunk<D>(kRowsPerLoad * g, 0)) * 16);
+        dma16(Mh, (unsigned)row * (unsigned)(D * 2) + chunk, ring[T % kRing] + (kRowsPerWave * wv + kRowsPerLoad * g) * (D * 2));
     };
-    auto publish_gate = [&](int T) {  // wave 0: raw c it loaded itself -> accumulator initial values
+    auto load_gate = [&](int T) __attribute__((always_inline)) {  // the 64 gate values of tile T's keys (every wave, same place)
+        const int j = max(j_hi - T, 0);
+        dma4(ch, (unsigned)min(j * kTileRows + lane, N - 1) * 4u, sm.craw[T % kRing]);
+    };
+    auto issue_k = [&](int T) __attribute__((always_inline)) {  // keys of tile T and their gate values
+        load_gate(T);
+#pragma unroll
+        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Kh, sm.k, T, g);
+    };
+    auto issue_v = [&](int T) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Vh, sm.v, T, g);
+    };
+    auto publish_gate = [&](int T) __attribute__((always_inline)) {  // wave 0: raw c it loaded itself -> accumulator initial values
         const int buf = T % kRing;
         sm.g[buf][lane] = (sm.craw[buf][lane] - cbase) * inv_scale;
     };
 
-    f32x16 o[DB];
-    float m, l;
-    // first two key tiles of the current query tile in flight, everything else of the ring idle
-    auto open_tile = [&]() __attribute__((always_inline)) {
-        issue_tile(0);
-        if (ntiles > 1) issue_tile(1);
-    };
+    f32x16 o[kQB][DB];
+    float m[kQB], l[kQB];
+    // the first key tile of the current query tile in flight
+    auto open_tile = [&]() __attribute__((always_inline)) { issue_k(0); };
     auto start_tile = [&]() __attribute__((always_inline)) {
-        // the first step multiplies pf = 0 with the last ring slot: make it finite
-        for (int o16 = tid * 16; o16 < kTileRows * D * 2; o16 += kFwdThreads * 16)
-            *reinterpret_cast<f32x4*>(sm.v[kRing - 1] + o16) = f32x4{0.f, 0.f, 0.f, 0.f};
         __builtin_amdgcn_s_waitcnt(0);
-        if (wv == 0) {
-            publish_gate(0);
-            if (ntiles > 1) publish_gate(1);
-        }
+        if (wv == 0) publish_gate(0);
         wg_barrier();
     };
     open_tile();
@@ -176,15 +190,15 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         gaddr = base + offsetof(FwdSmem<D>, g) + 16 * h;
     }
     constexpr int kTileBytes = kTileRows * D * 2;
-    auto read_k = [&](int kc, int disp) -> bf16x8 {
+    auto read_k = [&](int kc, int disp) __attribute__((always_inline)) -> bf16x8 {
         return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(kaddr[kc] + disp);
     };
-    auto read_vt = [&](int db, int disp) -> bf16x8 {
+    auto read_vt = [&](int db, int disp) __attribute__((always_inline)) -> bf16x8 {
         s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vaddr[db][0] + disp));
         s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vaddr[db][1] + disp));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    auto read_g = [&](f32x16& acc, int disp) {
+    auto read_g = [&](f32x16& acc, int disp) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const f32x4 g4 = *reinterpret_cast<__attribute__((address_space(3))) const f32x4*>(gaddr + disp + 32 * r);
@@ -195,181 +209,220 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         }
     };
 
-    f32x16 s[2];     // S^T of the two blocks of the current tile (0: upper 32 keys, 1: lower)
-    u32x4 pf[2][2];  // their probabilities as B operands (bf16 pairs)
-    bool pending;    // the previous tile left a P that still has to be multiplied into O
-    bool fresh;      // no tile of the current query tile has set this wave's reference exponent yet
-    constexpr bool kFirstTileShortcut = D == 64;
+    // ---- per-wave software pipeline over 32-key blocks.  Block n = 2 T + b (b = 0: upper half of tile T):
+    //   iteration n:   matrix pipe   S(n) = g + K Q^T           (K tile T)
+    //                                O   += V^T P(n-2)          (V tile T-1)
+    //                  vector unit   P(n-1) = exp2(S(n-1) sl - m sl), row sums
+    // S(n) lives in s[b], P(n) in pf[b], each for the kQB query blocks of the wave.  A wave runs the
+    // iterations n_first .. n_last + 2 of its own band [n_first, n_last]; there is one code path: outside the
+    // band the initial value of S is minus infinity (the band mask is applied to the accumulator's initial value,
+    // before the MFMA chain, and only on blocks that the diagonal or the window edge cuts or that lie outside),
+    // so such a block's probabilities are exactly zero and its products add nothing.
+    f32x16 s[2][kQB];
+    u32x4 pf[2][kQB][2];
+    int n_first, n_last;  // this wave's blocks (n_first > n_last: none)
     constexpr float kBig = 1.152921504606846976e18f;  // 2^60
 
-    // one key tile; the ring slot is a compile-time constant so that every LDS address is a
-    // loop-invariant register plus an immediate.  Block 0 is the upper half of the tile.
-    auto tile_step = [&](auto buf_c, int T) {
+    // two probabilities of block sb against the current reference exponent; their values are added to pa, pc
+    auto expo_pair = [&](const f32x16& sb, u32x4 (&pb)[2], int cc, float nm, float& pa, float& pc)
+                         __attribute__((always_inline)) {
+        f32x2 pr = {fast_exp2(fmaf(sb[2 * cc], sl, nm)), fast_exp2(fmaf(sb[2 * cc + 1], sl, nm))};
+        const bf16x2 pbf = __builtin_convertvector(pr, bf16x2);
+        // plain adds: the packed dot-product instructions run on the matrix pipe and would queue
+        // behind the MFMAs
+        pa += pr[0];
+        pc += pr[1];
+        pb[cc >> 2][cc & 3] = __builtin_bit_cast(unsigned, pbf);
+    };
+    // slow path: true maximum of the block (common to the two halves of the wave), new reference,
+    // rescale of O and l, exponentials once more.  Returns the block's row sum.
+    auto raise_reference = [&](const f32x16& sb, u32x4 (&pb)[2], int qb) __attribute__((always_inline)) -> float {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sb[v]);
+        mx = xhalf_max(mx);
+        const float mnew = fmaxf(m[qb], mx);
+        const float a = fast_exp2((m[qb] - mnew) * sl);
+        m[qb] = mnew;
+        l[qb] *= a;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[qb][db][v] *= a;
+        const float nm = -mnew * sl;
+        float pa = 0.f, pc = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) expo_pair(sb, pb, cc, nm, pa, pc);
+        return pa + pc;
+    };
+
+    // one iteration of the pipeline; ring slot and block are compile-time constants so that every LDS
+    // address is a loop-invariant register plus an immediate
+    auto iteration = [&](auto buf_c, auto blk_c, bool cut, int kb0, int T) __attribute__((always_inline)) {
         constexpr int buf = decltype(buf_c)::value;
-        constexpr int pbuf = (buf + kRing - 1) % kRing;  // slot of the previous tile
-        const int kt0 = (j_hi - T) * kTileRows;
-        bool act[2], full[2];
+        constexpr int b = decltype(blk_c)::value;
+        constexpr int pbuf = (buf + kRing - 1) % kRing;  // slot of the previous tile's values
+        constexpr int kdisp = buf * kTileBytes + 32 * (1 - b) * (D * 2);
+        constexpr int vdisp = pbuf * kTileBytes + 32 * (1 - b) * (D * 2);
+        constexpr int gdisp = buf * (kTileRows * 4) + 32 * (1 - b) * 4;
+        f32x16 (&sn)[kQB] = s[b];           // S(n), written here
+        f32x16 (&sx)[kQB] = s[1 - b];       // S(n-1), exponentiated here
+        u32x4 (&px)[kQB][2] = pf[1 - b];    // P(n-1), written here
+        u32x4 (&pp)[kQB][2] = pf[b];        // P(n-2), multiplied into O here
+        constexpr int kAhead = 4, NF = 2 * KC;   // fragments per iteration, each feeding kQB MFMAs
+        constexpr int kPairs = 8 * kQB;          // element pairs of the softmax, spread evenly over the NF steps
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int kb0 = kt0 + 32 * (1 - b);
-            act[b] = (T < ntiles) && (kb0 <= qw0 + 31) && (kb0 + 31 > qw0 - w) && (qw0 < N);
-            full[b] = (kb0 + 31 <= qw0) && (kb0 > qw0 + 31 - w);
-        }
-        const bool any_act = act[0] || act[1];
-        // slot (T+2) % kRing held tile T-2, whose V was last read in M(T-1)
-        const bool issue = T + 2 < ntiles;
-        if (issue) issue_tile(T + 2);
-
-        // ---------------- matrix phase M(T): one straight-line body.  A block outside the band
-        // of this wave still gets its S formed (never looked at); a wave with no pending P
-        // multiplies V by pf = 0.  Only a wave with neither skips the phase.
-        if (any_act || pending) {
-            constexpr int kAhead = 4, NS = 2 * KC, NP = 4 * DB, NF = NS + NP;
-            bf16x8 fr[NF];  // fragment f: K chunk of block f / KC for f < NS, else V^T fragment
-            auto fetch = [&](int f) {
-                if (f < NS) {
-                    fr[f] = read_k(f % KC, buf * kTileBytes + 32 * (1 - f / KC) * (D * 2));
-                } else {
-                    const int g = f - NS, b = g / (2 * DB), c2 = (g / DB) % 2, db = g % DB;
-                    fr[f] = read_vt(db, pbuf * kTileBytes + (32 * (1 - b) + 16 * c2) * (D * 2));
-                }
-            };
-            read_g(s[0], buf * (kTileRows * 4) + 32 * 4);
-            read_g(s[1], buf * (kTileRows * 4));
+        for (int qb = 0; qb < kQB; ++qb) read_g(sn[qb], gdisp);
+        if (__builtin_expect(cut, 0)) {  // the band mask, on the initial value: key i of the block for query t inside  t-w < i <= t, i >= 0
 #pragma unroll
-            for (int f = 0; f < kAhead; ++f) fetch(f);
-            __builtin_amdgcn_sched_group_barrier(0x100, 8 + kAhead, 0);
+            for (int qb = 0; qb < kQB; ++qb) {
+                const int t = t0 + 32 * qb;
 #pragma unroll
-            for (int i = 0; i < NF; ++i) {
-                if (i < NS) {
-                    s[i / KC] = mfma32(fr[i], qf[i % KC], s[i / KC]);
-                } else {
-                    const int g = i - NS, b = g / (2 * DB), c2 = (g / DB) % 2, db = g % DB;
-                    o[db] = mfma32(fr[i], __builtin_bit_cast(bf16x8, pf[b][c2]), o[db]);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (i + kAhead < NF) {
-                    fetch(i + kAhead);
-                    if (i + kAhead < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                for (int v = 0; v < 16; ++v) {
+                    const int i = kb0 + acc_row(v, h);
+                    sn[qb][v] = ((unsigned)i <= (unsigned)t && i > t - w) ? sn[qb][v] : -INFINITY;
                 }
             }
         }
-        // The one workgroup barrier of this tile: the second group takes it here, between its
-        // matrix and vector phase, the first group at the end of the step.  Both groups therefore
-        // run M(T) in the same interval (same ring slots), but the second group's X(T) falls into
-        // the next one, next to the first group's M(T+1).  Tile T+1 is first read after it.
-        if (grp == 1) {
-            if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
-            wg_barrier();
+        bf16x8 fr[NF];  // fragment i: even i: V^T fragment i / 2 of the PV product, odd i: K chunk i / 2
+        auto fetch = [&](int i) __attribute__((always_inline)) {
+            if (i & 1) {
+                fr[i] = read_k(i / 2, kdisp);
+            } else {
+                const int g = i / 2, c2 = g / DB, db = g % DB;
+                fr[i] = read_vt(db, vdisp + 16 * c2 * (D * 2));
+            }
+        };
+#pragma unroll
+        for (int f = 0; f < kAhead; ++f) fetch(f);
+        __builtin_amdgcn_sched_group_barrier(0x100, 3 * kAhead / 2, 0);
+        float nm[kQB], pa[kQB], pc[kQB];
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
+            nm[qb] = -m[qb] * sl;
+            pa[qb] = pc[qb] = 0.f;
         }
-
-        // ---------------- vector phase X(T)
-        if (any_act) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                if (act[b] && !full[b]) {
-                    const int kb0 = kt0 + 32 * (1 - b);
+        for (int i = 0; i < NF; ++i) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int i = kb0 + acc_row(v, h);
-                        const bool keep = (i <= t) && (i > t - w);
-                        s[b][v] = keep ? s[b][v] : -INFINITY;
-                    }
+            for (int qb = 0; qb < kQB; ++qb) {
+                if (i & 1) {
+                    sn[qb] = mfma32(fr[i], qf[qb][i / 2], sn[qb]);
+                } else {
+                    const int g = i / 2, c2 = g / DB, db = g % DB;
+                    o[qb][db] = mfma32(fr[i], __builtin_bit_cast(bf16x8, pp[qb][c2]), o[qb][db]);
                 }
             }
-            float tsum = 0.f;
-            auto exponentiate = [&]() __attribute__((always_inline)) {
-                const float nm = -m * sl;
-                float part[4] = {0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_sched_group_barrier(0x008, kQB, 0);
+            if (i + kAhead < NF) {
+                fetch(i + kAhead);
+                if ((i + kAhead) & 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+            // this wave's share of the step's tile loads, spread between the MFMAs so that the load unit's
+            // queue never fills: block 0 issues the keys of tile T+1 (and their gate values), block 1 the values of tile T
+            if (i == NF / 3 || i == 2 * NF / 3) {  // in two groups (inline assembly the scheduler cannot move work across)
+                const int g0 = i == NF / 3 ? 0 : kLoadsPerWave / 2, g1 = i == NF / 3 ? kLoadsPerWave / 2 : kLoadsPerWave;
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    if (act[b]) {
-#pragma unroll
-                        for (int cc = 0; cc < 8; ++cc) {
-                            f32x2 pr = {fast_exp2(fmaf(s[b][2 * cc], sl, nm)), fast_exp2(fmaf(s[b][2 * cc + 1], sl, nm))};
-                            const bf16x2 pb = __builtin_convertvector(pr, bf16x2);
-                            // plain adds: the packed dot-product instructions run on the matrix
-                            // pipe and would stall behind the other wave's MFMAs
-                            part[2 * b] += pr[0];
-                            part[2 * b + 1] += pr[1];
-                            pf[b][cc >> 2][cc & 3] = __builtin_bit_cast(unsigned, pb);
-                        }
+                for (int g = g0; g < g1; ++g) {
+                    if (b == 0) {
+                        if (g == 0) load_gate(T + 1);
+                        load_piece(Kh, sm.k, T + 1, g);
                     } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pf[b][0][e] = pf[b][1][e] = 0u;
+                        load_piece(Vh, sm.v, T, g);
                     }
                 }
-                tsum = (part[0] + part[1]) + (part[2] + part[3]);
-            };
-            // d = 64 (short bands, the first tile weighs more): a wave's first tile, whose reference exponent is
-            // still the initial one, goes straight to the slow path instead of trying the fast one first
-            const bool first = kFirstTileShortcut && fresh;
-            if (!first) exponentiate();
-            if (first || __builtin_amdgcn_ballot_w64(!(tsum <= kBig)) != 0) {
-                // slow path: true maximum of the tile, common to the two halves of the wave
-                float mx = -INFINITY;
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    if (act[b]) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[b][v]);
-                    }
-                mx = xhalf_max(mx);
-                const float mnew = fmaxf(m, mx);
-                const float a = fast_exp2((m - mnew) * sl);
-                m = mnew;
-                l *= a;
-                if (!first) {  // (O is still zero on a first tile)
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) o[db][v] *= a;
-                }
-                exponentiate();
             }
-            l += tsum;
-            fresh = false;
-        } else {
+            // the softmax of block n-1: pairs [i kPairs / NF, (i + 1) kPairs / NF) in this step
 #pragma unroll
-            for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
+            for (int pair = i * kPairs / NF; pair < (i + 1) * kPairs / NF; ++pair) {
+                const int qb = pair / 8, cc = pair % 8;
+                expo_pair(sx[qb], px[qb], cc, nm[qb], pa[qb], pc[qb]);
+            }
+            // (no scheduling groups for the vector work: left alone, the scheduler spreads it between the MFMAs)
         }
-        pending = any_act;
-        if (grp == 0) {
-            if (issue) __builtin_amdgcn_s_waitcnt(vmcnt_only(kBatch));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
-            if (wv == 0 && T + 1 < ntiles && T >= 1) publish_gate(T + 1);  // tiles 0, 1: prologue
-            wg_barrier();
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
+            float tsum = pa[qb] + pc[qb];
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(tsum <= kBig)) != 0, 0)) tsum = raise_reference(sx[qb], px[qb], qb);
+            l[qb] += tsum;
         }
     };
-    static_assert(kRing == 4, "the tile loop is unrolled over the ring");
+
+    // one key tile: two iterations, then the one workgroup barrier of the tile.  Step T reads the keys of
+    // tile T and the values of tile T-1; the keys of tile T+1 and the values of tile T are loaded meanwhile,
+    // into the slots whose last readers (step T-1) the previous barrier has seen off.
+    auto end_step = [&](int T) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+        if (wv == 0 && T + 1 < ntiles) publish_gate(T + 1);
+        wg_barrier();
+    };
+    // whole block (first key kb0, number n) inside the band of all queries of the wave?  (a block outside the band,
+    // at most one at either end of the steps a wave takes part in, runs fully masked)
+    auto is_full = [&](int kb0, int n) __attribute__((always_inline)) { return (kb0 + 31 <= qw0) && (kb0 > qw0 + 32 * kQB - 1 - w) && (n <= n_last); };
+    auto tile_step = [&](auto buf_c, int T) __attribute__((always_inline)) {
+        const int kt0 = (j_hi - T) * kTileRows;
+        iteration(buf_c, std::integral_constant<int, 0>{}, !is_full(kt0 + 32, 2 * T), kt0 + 32, T);
+        iteration(buf_c, std::integral_constant<int, 1>{}, !is_full(kt0, 2 * T + 1), kt0, T);
+        end_step(T);
+    };
+    // a step in which this wave has nothing to compute: only its share of the loads
+    auto load_step = [&](int T) __attribute__((always_inline)) {
+        issue_k(T + 1);
+        issue_v(T);
+        end_step(T);
+    };
+    static_assert(kRing == 2, "the tile loop is unrolled over the ring");
     for (;;) {  // query tiles of this workgroup
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < kQB; ++qb) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
-    m = kNegBig;
-    l = 0.0f;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) pf[0][0][e] = pf[0][1][e] = pf[1][0][e] = pf[1][1][e] = 0u;
-    pending = false;
-    fresh = true;
-    // T = ntiles is the drain step (only the PV product of the last tile)
-    for (int T = 0; T <= ntiles; T += 4) {
-        tile_step(std::integral_constant<int, 0>{}, T);
-        if (T + 1 > ntiles) break;
-        tile_step(std::integral_constant<int, 1>{}, T + 1);
-        if (T + 2 > ntiles) break;
-        tile_step(std::integral_constant<int, 2>{}, T + 2);
-        if (T + 3 > ntiles) break;
-        tile_step(std::integral_constant<int, 3>{}, T + 3);
+            for (int v = 0; v < 16; ++v) o[qb][db][v] = 0.0f;
+        m[qb] = kNegBig;
+        l[qb] = 0.0f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[b][qb][v] = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pf[b][qb][0][e] = pf[b][qb][1][e] = 0u;
+        }
+    }
+    {   // blocks of this wave's band, numbered in visiting order (descending keys from tile j_hi)
+        const int khi = min(qw0 + 32 * kQB - 1, N - 1), klo = max(0, qw0 - w + 1);
+        auto block_of = [&](int key) __attribute__((always_inline)) { return 2 * (j_hi - key / kTileRows) + 1 - (key % kTileRows) / 32; };
+        n_first = block_of(khi);
+        n_last = qw0 < N ? block_of(klo) : n_first - 3;
+    }
+    // T = ntiles is the drain step (softmax of the last block, PV products of the last tile)
+    {
+        // steps this wave computes in: T_first .. T_last (its blocks n_first .. n_last + 2); the others only load
+        const int T_first = min(n_first / 2, ntiles + 1), T_last = min((n_last + 2) / 2, ntiles);
+        int T = 0;
+        for (; T < T_first; ++T) load_step(T);
+        if (T <= T_last && (T & 1)) {
+            tile_step(std::integral_constant<int, 1>{}, T);
+            ++T;
+        }
+        for (; T + 1 <= T_last; T += 2) {
+            tile_step(std::integral_constant<int, 0>{}, T);
+            tile_step(std::integral_constant<int, 1>{}, T + 1);
+        }
+        if (T <= T_last) {
+            tile_step(std::integral_constant<int, 0>{}, T);
+            ++T;
+        }
+        for (; T <= ntiles; ++T) load_step(T);
     }
 
     // all LDS reads of this query tile are done (last barrier): open the next one before storing
-    const int t_done = t, bh_done = bh;
+    const int t_done = t0, bh_done = bh;
     const size_t head_done = head_off;
-    const float cq_done = cq;
+    float cq_done[kQB];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) cq_done[qb] = cq[qb];
     const bool more = tile_of(wg_step + 1) < total_tiles;
     if (more) {
         tile = tile_of(++wg_step);
@@ -377,19 +430,23 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         open_tile();
     }
     // ---- epilogue: O = O^T / l, L = ln2 * (m*sl + log2 l) - (c_t - c_base)
-    const float lt = xhalf_sum(l);  // the two halves of the wave hold complementary keys
-    if (t_done < N) {
-        const float inv = 1.0f / lt;
-        bf16_t* orow = O + head_done + (size_t)t_done * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < kQB; ++qb) {
+        const float lt = xhalf_sum(l[qb]);  // the two halves of the wave hold complementary keys
+        const int t = t_done + 32 * qb;
+        if (t < N) {
+            const float inv = 1.0f / lt;
+            bf16_t* orow = O + head_done + (size_t)t * D;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 o4 = {o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv,
-                            o[db][4 * g + 3] * inv};
-                *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(o4, bf16x4);
-            }
-        if (h == 0) L[(size_t)bh_done * N + t_done] = (m * sl + fast_log2(lt)) * kLn2 - cq_done;
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 o4 = {o[qb][db][4 * g] * inv, o[qb][db][4 * g + 1] * inv, o[qb][db][4 * g + 2] * inv,
+                                o[qb][db][4 * g + 3] * inv};
+                    *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(o4, bf16x4);
+                }
+            if (h == 0) L[(size_t)bh_done * N + t] = (m[qb] * sl + fast_log2(lt)) * kLn2 - cq_done[qb];
+        }
     }
     if (!more) break;
     start_tile();
@@ -406,7 +463,7 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
                                          lds_allowed))
         return e;
     const int num_cu = device_cu_count();
-    const int grid = total < num_cu ? total : num_cu;  // one resident workgroup per CU
+    const int grid = total < 2 * num_cu ? total : 2 * num_cu;  // two resident workgroups per CU
     ProfScope prof(kKernForward, s);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(grid), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w,
