@@ -206,18 +206,33 @@ int gfwa_version(void);
  * Instrumentation (not part of the method): per-kernel timing with HIP events recorded on the
  * caller's stream around every kernel the library launches.  gfwa_profile_enable(1) clears the
  * records and starts recording (at most 8192 launches are kept), gfwa_profile_enable(0) stops.
- * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 12), the
- * summed duration in milliseconds and the number of launches; n must be >= 12.  Kernel ids:
+ * gfwa_profile_read waits for the recorded events and returns, per kernel id k in [0, 13), the
+ * summed duration in milliseconds and the number of launches; n must be >= 13.  Kernel ids:
  * 0 gate prefix scan, 1 forward, 2 backward row-dot (D), 3 backward dK/dV, 4 backward dQ,
  * 5 gate-gradient reverse scan, 6 gate activation + prefix scan, 7 gate activation backward,
  * 8 decoding step (per-chunk partials), 9 decoding step (merge of the chunks), 10 and 11 the two
- * launches of gfwa_gate_prefix_stp (segment sums, scan of the segments);
+ * launches of gfwa_gate_prefix_stp (segment sums, scan of the segments), 12 the segment sums of the
+ * gate-gradient scan when the backward cuts few long rows into segments (its scan is then id 5);
  * gfwa_profile_kernel_name gives the same as text.
- * Not thread-safe; host memory only.
+ * An event pair costs a few microseconds on the stream: kernels of about ten microseconds read
+ * correspondingly longer than in a trace.  Not thread-safe; host memory only.
  */
 int gfwa_profile_enable(int on);
 int gfwa_profile_read(float *total_ms, int *launches, int n);
 const char *gfwa_profile_kernel_name(int k);
+
+/*
+ * Calibration (not part of the method): what the device at hand sustains, for the rooflines the
+ * attention kernels are reported against.
+ * gfwa_probe_mfma runs a loop of `iterations` x 16 bf16 32x32x16 MFMAs per wave on `workgroups`
+ * workgroups of 8 waves (two per SIMD; use a multiple of the number of compute units) and writes
+ * the floating-point operations of the launch to *flops (host memory, may be NULL); `sink` is one
+ * device float the kernel may write (it never does for these operands).  gfwa_probe_copy copies
+ * `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned) with plain 16-byte accesses:
+ * 2 * bytes of memory traffic.  Both only enqueue; the caller times them on its stream.
+ */
+int gfwa_probe_mfma(float *sink, int iterations, int workgroups, double *flops, gfwa_stream_t stream);
+int gfwa_probe_copy(const void *src, void *dst, size_t bytes, gfwa_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     gfwa_gate_prefix,
     gfwa_gate_prefix_stp,
     gfwa_gate_scan_workspace_bytes,
+    gfwa_probe_copy,
+    gfwa_probe_mfma,
     gfwa_profile_enable,
     gfwa_profile_kernel_name,
     gfwa_profile_read,

@@ -20,9 +20,9 @@ GFWA_BF16, GFWA_F32 = 0, 1
 
 EXPORTS = ("gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward", "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_backward",
            "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_decode_static", "gfwa_gate_scan_workspace_bytes", "gfwa_gate_prefix_stp",
-           "gfwa_strerror", "gfwa_version", "gfwa_profile_enable", "gfwa_profile_read",
+           "gfwa_strerror", "gfwa_version", "gfwa_probe_mfma", "gfwa_probe_copy", "gfwa_profile_enable", "gfwa_profile_read",
            "gfwa_profile_kernel_name")
-N_KERNELS = 12
+N_KERNELS = 13
 
 
 class GfwaError(RuntimeError):
@@ -75,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_gate_scan_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_gate_prefix_stp.argtypes = [fp, fp, f, fp, vp, ctypes.c_size_t, i, i, i, vp]
     lib.gfwa_gate_prefix_stp.restype = i
+    lib.gfwa_probe_mfma.argtypes = [fp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    lib.gfwa_probe_mfma.restype = i
+    lib.gfwa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.gfwa_probe_copy.restype = i
     lib.gfwa_strerror.argtypes = [i]
     lib.gfwa_strerror.restype = ctypes.c_char_p
     lib.gfwa_version.argtypes = []
@@ -404,6 +408,26 @@ def gfwa_decode_static(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: t
                                              o.data_ptr(), L.data_ptr(), B, H, Hkv, T, d, int(w), float(scale),
                                              _stream()))
     return o, L
+
+
+def gfwa_probe_mfma(sink: torch.Tensor, iterations: int, workgroups: int) -> float:
+    """Enqueue the pure bf16 MFMA loop; returns the floating-point operations of the launch."""
+    _need(sink, tuple(sink.shape), torch.float32, "sink")
+    flops = ctypes.c_double(0.0)
+    _check(load_library().gfwa_probe_mfma(sink.data_ptr(), int(iterations), int(workgroups), ctypes.byref(flops),
+                                          _stream()))
+    return float(flops.value)
+
+
+def gfwa_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Enqueue a plain copy of src into dst (same size, contiguous); returns the bytes copied."""
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("src and dst must be contiguous GPU tensors")
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("src and dst differ in size")
+    _check(load_library().gfwa_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()))
+    return nbytes
 
 
 def gfwa_profile_enable(on: bool) -> None:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgfwa.so")
-SOURCES = ["api.hip", "gate_scan.hip", "fp32_path.hip", "fwd_bf16.hip", "bwd_bf16.hip", "decode.hip"]
+SOURCES = ["api.hip", "gate_scan.hip", "fp32_path.hip", "fwd_bf16.hip", "bwd_bf16.hip", "decode.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU ops are kept off on the test machines
@@ -25,7 +25,7 @@ EXTRA_FLAGS = {
 }
 
 
-def build(verbose: bool = False, jobs: int = 5) -> str:
+def build(verbose: bool = False, jobs: int = 7) -> str:
     """Compile every source to an object (in parallel) and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")

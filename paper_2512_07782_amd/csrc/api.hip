@@ -152,9 +152,10 @@ int gfwa_forward_gqa(gfwa_dtype_t dt, const void* Q, const void* K, const void* 
 size_t gfwa_backward_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
     if (check_dims(B, H, N, d, w, true) != GFWA_OK) return 0;
     if (dt != GFWA_BF16 && dt != GFWA_F32) return 0;
-    // D, dc_col, dc_row: three fp32 vectors of B*H*N, each padded to 256 bytes
+    // D, dc_col, dc_row: three fp32 vectors of B*H*N, each padded to 256 bytes; then the segment sums of the
+    // gate-gradient scan (one fp64 per 4096 elements)
     const size_t one = (((size_t)B * H * N * sizeof(float)) + 255) & ~(size_t)255;
-    return 3 * one;
+    return 3 * one + ((gate_scan_workspace_bytes(B * H, N) + 255) & ~(size_t)255);
 }
 
 size_t gfwa_backward_fast_workspace_bytes(gfwa_dtype_t dt, int B, int H, int N, int d, int w) {
@@ -252,6 +253,20 @@ const char* gfwa_strerror(int code) {
 
 int gfwa_version(void) { return 100; }
 
+int gfwa_probe_mfma(float* sink, int iterations, int workgroups, double* flops, gfwa_stream_t stream) {
+    if (!sink) return GFWA_ERR_NULL;
+    if (iterations < 1 || workgroups < 1 || workgroups > (1 << 20) || iterations > (1 << 24)) return GFWA_ERR_DIM;
+    if (!aligned(sink, 4)) return GFWA_ERR_ALIGN;
+    return hip_status(probe_mfma(sink, iterations, workgroups, flops, stream));
+}
+
+int gfwa_probe_copy(const void* src, void* dst, size_t bytes, gfwa_stream_t stream) {
+    if (!src || !dst) return GFWA_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0) return GFWA_ERR_DIM;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return GFWA_ERR_ALIGN;
+    return hip_status(probe_copy(src, dst, bytes, stream));
+}
+
 int gfwa_profile_enable(int on) {
     g_prof.on = on != 0;
     if (g_prof.on) g_prof.used = 0;  // records stay readable after profiling is switched off
@@ -279,7 +294,8 @@ int gfwa_profile_read(float* total_ms, int* launches, int n) {
 const char* gfwa_profile_kernel_name(int k) {
     static const char* names[kKernCount] = {"gate_prefix_scan", "forward", "bwd_rowdot", "bwd_dkv", "bwd_dq",
                                             "gate_grad_scan", "gate_activation_prefix_scan",
-                                            "gate_activation_bwd", "decode_partial", "decode_combine", "scan_segment_sum", "scan_propagate"};
+                                            "gate_activation_bwd", "decode_partial", "decode_combine", "scan_segment_sum", "scan_propagate",
+                                            "gate_grad_segment_sum"};
     return (k >= 0 && k < kKernCount) ? names[k] : "";
 }
 

@@ -498,10 +498,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                     char* blk = ds_ws + (((size_t)bh * nqb + qb) * nslot + (kb - qb + nslot - 1)) * kSpillBlockBytes;
                     // streaming stores: the blocks are read once, by the next kernel, and must not push the
                     // Q and dO tiles the neighbouring workgroups are about to re-read out of the L2
-                    __builtin_nontemporal_store(dsf[0], reinterpret_cast<bf16x8*>(blk + spill_lane0));
-                    __builtin_nontemporal_store(dsf[1], reinterpret_cast<bf16x8*>(blk + spill_lane1));
-                    // the wait at the end of the tile counts on these two being issued by then
-                    asm volatile("" ::: "memory");
+                    // Written as instructions, not as stores the compiler may split, merge or move: the wait at the
+                    // end of the tile is s_waitcnt vmcnt(2), which leaves exactly these two in flight and therefore
+                    // counts on both having been issued after the tile's direct global->LDS loads and before it.
+                    stream_store16(blk + spill_lane0, dsf[0]);
+                    stream_store16(blk + spill_lane1, dsf[1]);
                 }
                 if (D != 128) {
 #pragma unroll
@@ -926,7 +927,9 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     float* Dv = ws;
     float* dc_col = ws + pad;
     float* dc_row = ws + 2 * pad;
-    char* ds_ws = reinterpret_cast<char*>(ws + 3 * pad);  // only with `spill`
+    double* scan_partial = reinterpret_cast<double*>(ws + 3 * pad);
+    const size_t scan_pad = (gate_scan_workspace_bytes(B * H, N) + 255) & ~(size_t)255;
+    char* ds_ws = reinterpret_cast<char*>(ws + 3 * pad) + scan_pad;  // only with `spill`
     constexpr int LPR = D / 8;
     const unsigned dot_blocks = (unsigned)((rows * LPR + 255) / 256);
     {
@@ -974,7 +977,7 @@ static hipError_t launch_bwd(const void* Q, const void* K, const void* V, const 
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return gate_grad_scan(dc_col, dc_row, dalpha, B * H, N, s);
+    return gate_grad_scan(dc_col, dc_row, dalpha, scan_partial, B * H, N, s);
 }
 
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,

@@ -248,7 +248,9 @@ hipError_t backward_f32(const float* Q, const float* K, const float* V, const fl
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return gate_grad_scan(dc_col, dc_row, dalpha, B * H, N, s);
+    // behind the three vectors as the workspace query sizes them (each padded to 256 bytes)
+    const size_t one = ((rows * sizeof(float)) + 255) & ~(size_t)255;
+    return gate_grad_scan(dc_col, dc_row, dalpha, reinterpret_cast<double*>(reinterpret_cast<char*>(ws) + 3 * one), B * H, N, s);
 }
 
 }  // namespace gfwa

@@ -57,8 +57,8 @@ enum ScanInput { kScanPlain = 0, kScanDiff = 1, kScanGate = 2 };
 
 // Logical position p of the scan maps to memory index p (forward) or N-1-p (reverse).
 // MODE kScanDiff: the scanned value is a[idx] - b[idx]; kScanGate: gate_alpha(a[idx], b[idx], eps).
-// With `partial` given (scan-then-propagate, forward scans only) a workgroup takes segment blockIdx.x % P
-// of row blockIdx.x / P, seg_len elements long, and starts from the sum of the row's earlier segments.
+// With `partial` given (scan-then-propagate) a workgroup takes segment blockIdx.x % P of row blockIdx.x / P,
+// seg_len logical positions long, and starts from the sum of the row's earlier segments.
 template <bool REVERSE, int MODE>
 __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __restrict__ a,
                                                                  const float* __restrict__ b,
@@ -162,37 +162,43 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
 // Phase 1 of scan-then-propagate (App. "Preprocessing via Scan-Then-Propagate"): the sum of every
 // segment, the activation recomputed on the fly when the input is (h, beta).  fp32 per thread over
 // its few elements, fp64 across the workgroup.
-template <int MODE>
+template <bool REVERSE, int MODE>
 __global__ __launch_bounds__(kScanThreads) void segment_sum_kernel(const float* __restrict__ a,
                                                                    const float* __restrict__ b,
                                                                    double* __restrict__ partial, int N, float eps,
                                                                    int seg_len, int P) {
-    static_assert(MODE == kScanPlain || MODE == kScanGate, "forward scans only");
     __shared__ double wave_sum[kScanWaves];
     const int seg = (int)(blockIdx.x % P);
     const size_t row = (size_t)(blockIdx.x / P) * N;
     const int begin = seg * seg_len, end = min(N, begin + seg_len);
     const float* ar = a + row;
-    const float* br = MODE == kScanGate ? b + row : nullptr;
+    const float* br = MODE != kScanPlain ? b + row : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const uintptr_t bits = (uintptr_t)a | (MODE == kScanGate ? (uintptr_t)b : (uintptr_t)0);
+    const uintptr_t bits = (uintptr_t)a | (MODE != kScanPlain ? (uintptr_t)b : (uintptr_t)0);
     const bool vec = (N % 4 == 0) && ((bits & 15) == 0);
     float acc = 0.f;
-    for (int base = begin; base < end; base += kScanChunk) {
+    for (int base = begin; base < end; base += kScanChunk) {  // logical positions, as in scan_rows_kernel
         const int p0 = base + 4 * tid;
         if (vec && p0 + 3 < end) {
-            float4 x = *reinterpret_cast<const float4*>(ar + p0);
+            const int idx = REVERSE ? N - 4 - p0 : p0;
+            float4 x = *reinterpret_cast<const float4*>(ar + idx);
             if (MODE == kScanGate) {
-                const float4 y = *reinterpret_cast<const float4*>(br + p0);
+                const float4 y = *reinterpret_cast<const float4*>(br + idx);
                 x.x = gate_alpha(x.x, y.x, eps); x.y = gate_alpha(x.y, y.y, eps);
                 x.z = gate_alpha(x.z, y.z, eps); x.w = gate_alpha(x.w, y.w, eps);
+            } else if (MODE == kScanDiff) {
+                const float4 y = *reinterpret_cast<const float4*>(br + idx);
+                x.x -= y.x; x.y -= y.y; x.z -= y.z; x.w -= y.w;
             }
             acc += (x.x + x.y) + (x.z + x.w);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int p = p0 + e;
-                if (p < end) acc += MODE == kScanGate ? gate_alpha(ar[p], br[p], eps) : ar[p];
+                if (p < end) {
+                    const int idx = REVERSE ? N - 1 - p : p;
+                    acc += MODE == kScanGate ? gate_alpha(ar[idx], br[idx], eps) : MODE == kScanDiff ? ar[idx] - br[idx] : ar[idx];
+                }
             }
         }
     }
@@ -247,9 +253,9 @@ hipError_t gate_prefix_stp(const float* in, const float* beta, float eps, float*
     {
         ProfScope prof(kKernScanSegmentSum, s);
         if (beta != nullptr)
-            hipLaunchKernelGGL((segment_sum_kernel<kScanGate>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
+            hipLaunchKernelGGL((segment_sum_kernel<false, kScanGate>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
         else
-            hipLaunchKernelGGL((segment_sum_kernel<kScanPlain>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
+            hipLaunchKernelGGL((segment_sum_kernel<false, kScanPlain>), grid, block, 0, s, in, beta, partial, N, eps, seg_len, P);
     }
     {
         ProfScope prof(kKernScanPropagate, s);
@@ -316,8 +322,28 @@ hipError_t gate_activation_backward(const float* hpre, const float* beta, float 
     return hipGetLastError();
 }
 
-hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
+// Few long rows leave most of the chip idle with one workgroup per row: then the rows are cut into segments
+// (scan-then-propagate, as gate_prefix_stp does for the forward prefix), which needs `partial`.
+bool gate_grad_scan_wants_segments(int rows, int N) {
+    return rows < device_cu_count() && N >= 2 * kScanChunk;
+}
+
+hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, double* partial, int rows, int N,
                           hipStream_t s) {
+    if (partial != nullptr && gate_grad_scan_wants_segments(rows, N)) {
+        int seg_len = 0;
+        const int P = scan_segments(rows, N, &seg_len);
+        const dim3 grid((unsigned)(rows * P)), block(kScanThreads);
+        {
+            ProfScope prof(kKernGateGradSegmentSum, s);
+            hipLaunchKernelGGL((segment_sum_kernel<true, kScanDiff>), grid, block, 0, s, dc_col, dc_row, partial, N, 0.f,
+                               seg_len, P);
+        }
+        ProfScope prof(kKernGateGrad, s);
+        hipLaunchKernelGGL((scan_rows_kernel<true, kScanDiff>), grid, block, 0, s, dc_col, dc_row, dalpha, N, 0.f,
+                           (const double*)partial, seg_len, P);
+        return hipGetLastError();
+    }
     ProfScope prof(kKernGateGrad, s);
     hipLaunchKernelGGL((scan_rows_kernel<true, kScanDiff>), dim3(rows), dim3(kScanThreads), 0, s, dc_col,
                        dc_row, dalpha, N, 0.f);

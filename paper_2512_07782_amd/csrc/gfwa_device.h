@@ -138,6 +138,11 @@ __device__ __forceinline__ void dma4(const void* sbase, unsigned voff, const voi
         : "s"(lds_addr), "v"(voff), "s"(sbase)
         : "memory");
 }
+// One 16-byte non-temporal global store per lane, issued exactly here in program order (inline assembly with a
+// memory clobber): for code that counts its outstanding vector-memory operations by hand.
+__device__ __forceinline__ void stream_store16(void* p, bf16x8 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+}
 // s_waitcnt that waits only for vmcnt <= n (gfx9 encoding: expcnt and lgkmcnt fields left at max)
 constexpr int vmcnt_only(int n) { return 0x0f70 | (n & 0xf) | ((n >> 4) << 14); }
 

@@ -16,8 +16,9 @@ hipError_t gate_activation_backward(const float* hpre, const float* beta, float 
 size_t gate_scan_workspace_bytes(int rows, int N);
 hipError_t gate_prefix_stp(const float* in, const float* beta, float eps, float* c, double* partial, int rows,
                            int N, hipStream_t s);
-// dalpha = reverse inclusive prefix sum of (col - row) along N.
-hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, int rows, int N,
+// dalpha = reverse inclusive prefix sum of (col - row) along N.  partial: gate_scan_workspace_bytes(rows, N) of
+// scratch (or nullptr); with it, few long rows are scanned in segments.
+hipError_t gate_grad_scan(const float* dc_col, const float* dc_row, float* dalpha, double* partial, int rows, int N,
                           hipStream_t s);
 
 // Q, O, dO, dQ: [B,H,N,d]; K, V, dK, dV: [B,Hkv,N,d] with Hkv dividing H (query head h reads head h / (H/Hkv));
@@ -28,7 +29,7 @@ hipError_t forward_f32(const float* Q, const float* K, const float* V, const flo
                        float* L, int B, int H, int Hkv, int N, int d, int w, float scale, hipStream_t s);
 
 // Workspace layout of the backward: three fp32 vectors of B*H*N (each padded to 256 bytes): D, dc_col,
-// dc_row; with `spill` (bf16, d = 128 only) backward_bf16_spill_bytes() more for the dS blocks.
+// dc_row; gate_scan_workspace_bytes(B*H, N) (padded to 256) of segment sums for the gate-gradient scan; with `spill` (bf16, d = 128 only) backward_bf16_spill_bytes() more for the dS blocks.
 size_t backward_bf16_spill_bytes(int B, int H, int N, int d, int w);  // 0: no such variant for this shape
 hipError_t backward_bf16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                          const float* c, const float* L, void* dQ, void* dK, void* dV, float* dalpha,
@@ -50,10 +51,14 @@ hipError_t decode(bool bf16, const void* q, const void* Kc, const void* Vc, floa
 constexpr size_t kDecodeStaticBytes = (size_t)32 << 20;
 hipError_t decode_static_scratch(float** ptr);
 
+// Calibration kernels (probe.hip): a pure bf16 MFMA loop and a plain 16-byte copy.
+hipError_t probe_mfma(float* sink, int iterations, int workgroups, double* flops, hipStream_t s);
+hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).
 enum KernelId { kKernGatePrefix = 0, kKernForward, kKernRowDot, kKernDkv, kKernDq, kKernGateGrad, kKernGateActPrefix,
                 kKernGateActBwd, kKernDecode, kKernDecodeCombine, kKernScanSegmentSum,
-                kKernScanPropagate, kKernCount };
+                kKernScanPropagate, kKernGateGradSegmentSum, kKernCount };
 
 // Per-device launch set-up, done once per device and kernel (`done`: one bit per device id, owned by the caller):
 // lets `kernel` use `bytes` of dynamic LDS on the current device.

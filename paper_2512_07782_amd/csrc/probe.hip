@@ -1,0 +1,58 @@
+// Two measurement kernels that calibrate the rooflines the attention kernels are held against: what the
+// matrix cores and the memory system of the device at hand actually sustain (not part of the method).
+//   * a loop of nothing but v_mfma_f32_32x32x16_bf16 on every SIMD of the chip: the achievable bf16 MFMA rate
+//     at the clock the part settles to under that load;
+//   * a plain copy with 16-byte accesses: the achievable HBM rate, and the known-size reference the
+//     FETCH_SIZE / WRITE_SIZE counters are scaled by.
+#include "gfwa_device.h"
+#include "gfwa_internal.h"
+
+namespace gfwa {
+
+constexpr int kProbeThreads = 512;  // 8 waves: two per SIMD
+constexpr int kProbeUnroll = 16;    // MFMAs per loop iteration and wave
+
+__global__ __launch_bounds__(kProbeThreads) void probe_mfma_kernel(float* __restrict__ sink, int iterations) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
+    bf16x8 x, y;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        x[e] = (bf16_t)(0.001f * (float)((threadIdx.x + e) & 31));
+        y[e] = (bf16_t)(0.002f * (float)((threadIdx.x + 3 * e) & 15));
+    }
+    for (int it = 0; it < iterations; ++it)
+#pragma unroll
+        for (int i = 0; i < kProbeUnroll; ++i) acc[i % 4] = mfma32(x, y, acc[i % 4]);
+    float s = 0.f;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[a][v];
+    if (s == -1.0f) sink[0] = s;  // never true (all terms are >= 0): keeps the loop alive without a store
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Launches the MFMA loop on `workgroups` workgroups of 8 waves; *flops receives the floating-point operations
+// the launch performs (2 * 32 * 32 * 16 per MFMA).
+hipError_t probe_mfma(float* sink, int iterations, int workgroups, double* flops, hipStream_t s) {
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, s, sink, iterations);
+    if (flops) *flops = 2.0 * 32 * 32 * 16 * kProbeUnroll * (double)iterations * (kProbeThreads / 64) * (double)workgroups;
+    return hipGetLastError();
+}
+
+hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    const int cus = device_cu_count();
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(cus * 16), dim3(256), 0, s, (const u32x4*)src, (u32x4*)dst, n16);
+    return hipGetLastError();
+}
+
+}  // namespace gfwa

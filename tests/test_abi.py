@@ -26,7 +26,7 @@ def test_header_symbols_are_exported(lib):
     assert names == sorted(["gfwa_gate_prefix", "gfwa_gate_activation_prefix", "gfwa_gate_activation_backward",
                             "gfwa_forward", "gfwa_backward_workspace_bytes", "gfwa_backward_fast_workspace_bytes", "gfwa_forward_gqa", "gfwa_backward_gqa", "gfwa_decode_workspace_bytes", "gfwa_decode", "gfwa_decode_static", "gfwa_gate_scan_workspace_bytes",
                             "gfwa_gate_prefix_stp",
-                            "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_profile_enable",
+                            "gfwa_backward", "gfwa_strerror", "gfwa_version", "gfwa_probe_mfma", "gfwa_probe_copy", "gfwa_profile_enable",
                             "gfwa_profile_read", "gfwa_profile_kernel_name"])
     for n in names:
         assert hasattr(lib, n), n
@@ -95,6 +95,12 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_decode_static(*decs(q=odd)) == -4
     assert lib.gfwa_decode_workspace_bytes(4096, 4, 8192, 128, 8192) > 32 << 20
     assert lib.gfwa_decode_static(*decs(B=4096, T=8192, w=8192)) == -5
+    # calibration kernels
+    assert lib.gfwa_probe_mfma(None, 10, 256, None, None) == -1
+    assert lib.gfwa_probe_mfma(good, 0, 256, None, None) == -2
+    assert lib.gfwa_probe_copy(good, None, 1024, None) == -1
+    assert lib.gfwa_probe_copy(good, good, 1000, None) == -2
+    assert lib.gfwa_probe_copy(odd, good, 1024, None) == -4
     # forward
     args = lambda **kw: [kw.get("dt", 0), kw.get("Q", good), good, good, kw.get("c", good), good, good,
                          kw.get("B", 1), 2, kw.get("N", 64), kw.get("d", 128), kw.get("w", 16), f, None]
