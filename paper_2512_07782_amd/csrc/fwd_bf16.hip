@@ -49,8 +49,14 @@ namespace gfwa {
 
 constexpr int kFwdWaves = 4;
 constexpr int kFwdThreads = 64 * kFwdWaves;
-constexpr int kQB = 1;                           // 32-query blocks per wave
-constexpr int kFwdBR = 32 * kQB * kFwdWaves;     // queries per workgroup
+// 32-query blocks per wave.  One: at d = 128 that is the register budget of two waves per SIMD; at d = 64 two blocks
+// fit (254 registers, every K and V fragment read from LDS then feeds two MFMAs) but measured slower, 84 us against
+// 74 us on the LM-scale workload: the 256-query tile staggers the waves' bands further and the waves run out of
+// independent work to cover each other.
+template <int D>
+constexpr int kQueryBlocks = 1;
+template <int D>
+constexpr int kFwdBR = 32 * kQueryBlocks<D> * kFwdWaves;  // queries per workgroup
 constexpr int kRing = 2;                         // K and V tile slots each: one being read, one in flight
 
 template <int D>
@@ -61,7 +67,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ c, bf16_t* __restrict__ O, float* __restrict__ L, int N, int w,
     float scale_log2, int num_qtiles, int total_tiles, int H, int G) {
-    constexpr int BR = kFwdBR;
+    constexpr int kQB = kQueryBlocks<D>;
+    constexpr int BR = kFwdBR<D>;
     constexpr int KC = D / 16;  // MFMA k-chunks along the head dimension
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
     using Loader = TilePairLoader<D, kFwdWaves>;
@@ -456,7 +463,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
 template <int D>
 static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const float* c, void* O,
                              float* L, int B, int H, int Hkv, int N, int w, float scale, hipStream_t s) {
-    const int num_qtiles = (N + kFwdBR - 1) / kFwdBR;
+    const int num_qtiles = (N + kFwdBR<D> - 1) / kFwdBR<D>;
     const int total = B * H * num_qtiles;
     static DeviceOnce lds_allowed;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D>), sizeof(FwdSmem<D>),
