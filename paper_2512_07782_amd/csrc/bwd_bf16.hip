@@ -288,12 +288,13 @@ constexpr int kSpillBlockBytes = 2048;
 // SIMD leave 256 registers per wave: the dK, dV accumulators (128) and
 // S, dP (32) stay, the K and V fragments do not - the 128 keys of K and V are staged in LDS once per
 // workgroup and read as B operands like the Q and dO tiles are read as A operands.  At the end the
-// two waves of a key group add their accumulators through LDS.
+// two waves of a key group trade halves of their accumulators through LDS: one ends with the whole dK,
+// the other with the whole dV, and each stores its matrix.
 template <int D>
 struct Dkv8Smem {
     union {
         DkvSmem<D> t;
-        float red[4][16 * (D / 32)][64];  // [key group][accumulator register][lane]
+        float red[4][16 * (D / 32)][64];  // exchange space of the final reduction (64 KB at d = 128), over the tile buffers
     };
     TilePairSmem<D> kv;  // a = the two 64-key tiles of K, b = of V
     float colred[4][32];
@@ -556,43 +557,60 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
         }
     }  // query heads of the group
 
-    // the two waves of a key group add their accumulators through LDS (the tile buffers are free now)
+    // The two waves of a key group hold partial dK and dV (one 32-query block of every tile each).  They trade
+    // halves through LDS (the tile buffers are free now): the wave of half 0 ends up with the whole dK, the wave
+    // of half 1 with the whole dV, and each stores its matrix.  Two sub-passes of two 32-column blocks each, so
+    // that the eight waves' pieces fit the 64 KB; 16-byte LDS accesses, [wave][register group][lane].
+    {
+        f32x4* xch = reinterpret_cast<f32x4*>(&sm8.red[0][0][0]);
+        constexpr int kGroups = 8;  // register groups of 4 per sub-pass and wave: 2 blocks x 16 registers
+        const int ow = half == 0 ? 4 + ((kg + 2) & 3) : kg;  // the other wave of this key group
+        auto put = [&](const f32x16 (&arr)[DB], int sub) __attribute__((always_inline)) {
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        __syncthreads();
-        if (half == 1) {
+            for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sm8.red[kg][16 * db + v][lane] = pass == 0 ? dk_acc[db][v] : dv_acc[db][v];
-        }
-        __syncthreads();
-        if (half == 0) {
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    if (pass == 0) dk_acc[db][v] += sm8.red[kg][16 * db + v][lane];
-                    else dv_acc[db][v] += sm8.red[kg][16 * db + v][lane];
+                for (int g = 0; g < 4; ++g) {
+                    const f32x16& a = arr[2 * sub + b2];
+                    xch[(wv * kGroups + 4 * b2 + g) * 64 + lane] = f32x4{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
                 }
+        };
+        auto add = [&](f32x16 (&arr)[DB], int sub) __attribute__((always_inline)) {
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 x = xch[(ow * kGroups + 4 * b2 + g) * 64 + lane];
+                    f32x16& a = arr[2 * sub + b2];
+                    a[4 * g] += x[0];
+                    a[4 * g + 1] += x[1];
+                    a[4 * g + 2] += x[2];
+                    a[4 * g + 3] += x[3];
+                }
+        };
+#pragma unroll
+        for (int sub = 0; sub < DB / 2; ++sub) {
+            __syncthreads();
+            if (half == 0) put(dv_acc, sub);
+            else put(dk_acc, sub);
+            __syncthreads();
+            if (half == 0) add(dk_acc, sub);
+            else add(dv_acc, sub);
         }
     }
-    if (half == 1) return;
 
     if (key < N) {
-        bf16_t* dkrow = dK + head_off + (size_t)key * D;
-        bf16_t* dvrow = dV + head_off + (size_t)key * D;
+        auto store_rows = [&](bf16_t* M, const f32x16 (&acc)[DB], float f) __attribute__((always_inline)) {
+            bf16_t* row = M + head_off + (size_t)key * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 k4 = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale,
-                            dk_acc[db][4 * g + 2] * scale, dk_acc[db][4 * g + 3] * scale};
-                f32x4 v4 = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2],
-                            dv_acc[db][4 * g + 3]};
-                *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(k4, bf16x4);
-                *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(v4, bf16x4);
-            }
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 x4 = {acc[db][4 * g] * f, acc[db][4 * g + 1] * f, acc[db][4 * g + 2] * f, acc[db][4 * g + 3] * f};
+                    *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(x4, bf16x4);
+                }
+        };
+        if (half == 0) store_rows(dK, dk_acc, scale);
+        else store_rows(dV, dv_acc, 1.0f);
     }
 }
 
