@@ -598,19 +598,12 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
         }
     }
 
-    if (key < N) {
-        auto store_rows = [&](bf16_t* M, const f32x16 (&acc)[DB], float f) __attribute__((always_inline)) {
-            bf16_t* row = M + head_off + (size_t)key * D;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4 x4 = {acc[db][4 * g] * f, acc[db][4 * g + 1] * f, acc[db][4 * g + 2] * f, acc[db][4 * g + 3] * f};
-                    *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(x4, bf16x4);
-                }
-        };
-        if (half == 0) store_rows(dK, dk_acc, scale);
-        else store_rows(dV, dv_acc, 1.0f);
+    // Each wave stores its matrix as whole lines, through 4 KB of the K/V staging area (free since the last tile).
+    {
+        char* stage = sm8.kv.a[0] + 4096 * wv;
+        const size_t row0 = head_off + (size_t)kw0 * D;
+        if (half == 0) store_acc_rows<DB>(dk_acc, scale, stage, dK + row0, N - kw0, lane);
+        else store_acc_rows<DB>(dv_acc, 1.0f, stage, dV + row0, N - kw0, lane);
     }
 }
 

@@ -130,4 +130,38 @@ __device__ __forceinline__ void acc_init_rows(f32x16& acc, const float* vec, int
     }
 }
 
+// A 32-row block of a bf16 matrix with 32 DB columns, held as DB accumulators in which lane l owns row l % 32
+// and register v of accumulator db column 32 db + 8 (v / 4) + 4 (l / 32) + v % 4, goes to global memory as whole
+// 128-byte lines: straight from the registers a store instruction would touch 32 rows with 16 bytes each, and
+// the memory pipeline takes such an instruction one line at a time.  The block passes through `stage`, 4 KB
+// of LDS private to the wave, 64 columns at a time: 8-byte writes in accumulator order, 16-byte reads in row
+// order (16-byte chunks XOR-swizzled by row pair, two-way conflicts on the writes, none on the reads).
+// g0 = row 0, column 0 of the block; rows at or beyond rows_valid are not stored.
+template <int DB>
+__device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f, char* stage, bf16_t* g0,
+                                               int rows_valid, int lane) {
+    const int lk = lane & 31, h = lane >> 5;
+    char* wr = stage + lk * 128 + 8 * h;
+    const int wsw = (lk >> 1) & 7;
+#pragma unroll
+    for (int hf = 0; hf < DB / 2; ++hf) {
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x16& a = acc[2 * hf + b2];
+                const f32x4 x4 = {a[4 * g] * f, a[4 * g + 1] * f, a[4 * g + 2] * f, a[4 * g + 3] * f};
+                *reinterpret_cast<bf16x4*>(wr + ((4 * b2 + g) ^ wsw) * 16) = __builtin_convertvector(x4, bf16x4);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wave's writes are in LDS before its lanes read each other's
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 8 * i + (lane >> 3), q = lane & 7;
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + r * 128 + ((q ^ ((r >> 1) & 7)) * 16));
+            if (r < rows_valid) *reinterpret_cast<bf16x8*>(g0 + (size_t)r * (32 * DB) + 64 * hf + 8 * q) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next 64 columns overwrite the stage
+    }
+}
+
 }  // namespace gfwa
