@@ -249,20 +249,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_bf16_kernel(
         if (key < N && h == 0) dc_col[(size_t)bh * N + key] = cs;
     }  // query heads of the group
 
-    if (key < N) {
-        bf16_t* dkrow = dK + head_off + (size_t)key * D;
-        bf16_t* dvrow = dV + head_off + (size_t)key * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 k4 = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale,
-                            dk_acc[db][4 * g + 2] * scale, dk_acc[db][4 * g + 3] * scale};
-                f32x4 v4 = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2],
-                            dv_acc[db][4 * g + 3]};
-                *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(k4, bf16x4);
-                *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(v4, bf16x4);
-            }
+    // dK and dV as whole lines, through 4 KB per wave of the tile buffers (free since the last barrier)
+    {
+        char* stage = sm.qg.a[0] + 4096 * wv;
+        const size_t row0 = head_off + (size_t)kw0 * D;
+        store_acc_rows<DB>(dk_acc, scale, stage, dK + row0, N - kw0, lane);
+        store_acc_rows<DB>(dv_acc, 1.0f, stage, dV + row0, N - kw0, lane);
     }
 }
 
@@ -772,18 +764,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_bf16_kernel(
     }
 
     const float rs = xhalf_sum(rowsum);
-    if (t < N) {
-        bf16_t* row = dQ + head_off + (size_t)t * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale, dq_acc[db][4 * g + 2] * scale,
-                            dq_acc[db][4 * g + 3] * scale};
-                *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(q4, bf16x4);
-            }
-        if (h == 0) dc_row[(size_t)bh * N + t] = rs;
-    }
+    if (t < N && h == 0) dc_row[(size_t)bh * N + t] = rs;
+    // dQ as whole lines, through 4 KB per wave of the tile buffers (free since the last barrier)
+    store_acc_rows<DB>(dq_acc, scale, sm.kv.a[0] + 4096 * wv, dQ + head_off + (size_t)qw0 * D, N - qw0, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -908,18 +891,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_spill_bf16_kernel(
     }
 
     const float rs = xhalf_sum(rowsum);
-    if (t < N) {
-        bf16_t* row = dQ + head_off + (size_t)t * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 q4 = {dq_acc[db][4 * g] * scale, dq_acc[db][4 * g + 1] * scale, dq_acc[db][4 * g + 2] * scale,
-                            dq_acc[db][4 * g + 3] * scale};
-                *reinterpret_cast<bf16x4*>(row + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(q4, bf16x4);
-            }
-        if (h == 0) dc_row[(size_t)bh * N + t] = rs;
-    }
+    if (t < N && h == 0) dc_row[(size_t)bh * N + t] = rs;
+    // dQ as whole lines, through this wave's own block buffer (its last block was consumed above)
+    store_acc_rows<DB>(dq_acc, scale, sm.ds[0][wv][0], dQ + head_off + (size_t)qw0 * D, N - qw0, lane);
 }
 
 size_t backward_bf16_spill_bytes(int B, int H, int N, int d, int w) {

@@ -441,19 +441,11 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
     for (int qb = 0; qb < kQB; ++qb) {
         const float lt = xhalf_sum(l[qb]);  // the two halves of the wave hold complementary keys
         const int t = t_done + 32 * qb;
-        if (t < N) {
-            const float inv = 1.0f / lt;
-            bf16_t* orow = O + head_done + (size_t)t * D;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4 o4 = {o[qb][db][4 * g] * inv, o[qb][db][4 * g + 1] * inv, o[qb][db][4 * g + 2] * inv,
-                                o[qb][db][4 * g + 3] * inv};
-                    *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g + 4 * h) = __builtin_convertvector(o4, bf16x4);
-                }
-            if (h == 0) L[(size_t)bh_done * N + t] = (m[qb] * sl + fast_log2(lt)) * kLn2 - cq_done[qb];
-        }
+        const float inv = 1.0f / lt;
+        if (t < N && h == 0) L[(size_t)bh_done * N + t] = (m[qb] * sl + fast_log2(lt)) * kLn2 - cq_done[qb];
+        // O as whole lines, through 4 KB per wave of the V ring (idle until the first step of the next tile)
+        const int row0 = t - lq;
+        store_acc_rows<DB>(o[qb], inv, sm.v[0] + 4096 * wv, O + head_done + (size_t)row0 * D, N - row0, lane);
     }
     if (!more) break;
     start_tile();
