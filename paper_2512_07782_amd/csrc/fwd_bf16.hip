@@ -1,29 +1,35 @@
 // GatedFWA fused forward for bf16 storage on gfx950 (paper Alg. 2, re-designed for CDNA4).
 //
-// One workgroup of 4 waves per CU (one wave per SIMD, with the whole register file of its SIMD) owns a
-// tile of 256 consecutive queries of one (b,h); a wave owns 64 of them as two 32-query blocks.  Key/value
-// tiles of 64 keys travel global -> LDS by direct loads (no staging registers, no LDS stores) through a
-// ring of kRing buffers, and only the tiles that intersect the band [q0-w+1, q0+255] are visited; inside
-// a tile every wave skips the 32-key blocks that lie wholly outside the band of its own queries, and
-// masks only the blocks the band edge or the diagonal cuts.
+// Workgroups of 4 waves, two resident per CU (two waves per SIMD, 256 registers each), persistent: a
+// workgroup takes one tile of 128 consecutive queries of one (b,h) after another, and a wave owns one block of
+// 32 of them.  Key/value tiles of 64 keys travel global -> LDS by direct loads (no staging registers, no LDS
+// stores) through rings of two K and two V slots; only the tiles that intersect the band [q0-w+1, q0+127] are
+// visited, from the diagonal backwards.  Inside a tile a wave computes only in the steps that hold blocks of its
+// own band (in the others it just issues its share of the loads) and masks only the blocks the band edge or
+// the diagonal cuts.
 //
-// The products are formed transposed so that a lane owns one query of each of its two blocks:
+// The products are formed transposed so that a lane owns one query:
 //   S^T[key][query]  = g[key] + K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
 //   O^T[dd][query]  += V_tile^T (A operand, LDS transposing read)  x  P^T (B operand = the S^T
 //                      accumulator registers converted to bf16 in place)
 // so the row max / row sum of the online softmax are in-lane plus one exchange between the two
-// halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.  Every K
-// and V fragment read from LDS feeds two MFMAs (one per query block).
+// halves of the wave, the rescale factor is a per-lane scalar, and P never leaves registers.
 //
 // Software pipeline inside the wave.  With blocks of 32 keys numbered n in visiting order, iteration n
 // issues, as one straight-line instruction stream,
-//   matrix pipe:  S(n) = g + K Q^T      and      O += V^T P(n-2)          (32 MFMAs at d = 128)
+//   matrix pipe:  S(n) = g + K Q^T      and      O += V^T P(n-2)          (16 MFMAs at d = 128)
 //   vector unit:  P(n-1) = exp2(S(n-1) * sl - m * sl), row sums
 //   LDS:          the fragments of the MFMAs four steps ahead
+//   load unit:    this wave's share of the keys of tile T+1 (first block of a tile) or of the values of
+//                 tile T (second block), in two groups between the MFMAs
 // Nothing in an iteration depends on anything else in it, so the MFMAs issue back to back while the
 // exponentials of the previous block and the fragment reads of the next MFMAs fill the issue slots
 // between them (an MFMA occupies the matrix pipe for 32 cycles; about five vector and two LDS
-// instructions fit beside it).  One workgroup barrier per key tile hands the ring slots over.
+// instructions fit beside it).  A step is the two iterations of one key tile; one workgroup barrier per
+// step hands the ring slots over.  The V tile of step T is requested in step T and first read in step
+// T+1 (by the PV products, which lag two blocks), the K tile of step T+1 is requested in step T.
+// When a tile is finished the first key tile of the next one is requested before O is stored, and O
+// leaves as whole 128-byte lines through the idle V ring.
 //
 // The gate bias rides in the MFMA accumulator: S is initialised with g_i = (c_i - c_base) / scale
 // straight from LDS before the K Q^T chain, so S = q.k + g_i and the probability is one fused
@@ -106,6 +112,14 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         cbase = ch[q0];
         qw0 = q0 + 32 * kQB * wv;  // first query of this wave
         t0 = qw0 + lq;             // this lane's query in block 0; block qb: t0 + 32 qb
+        // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
+        const int k_lo = max(0, q0 - w + 1);
+        const int k_hi = min(N, q0 + BR) - 1;
+        j_lo = k_lo / kTileRows;
+        j_hi = k_hi / kTileRows;
+        ntiles = j_hi - j_lo + 1;
+    };
+    auto load_queries = [&]() __attribute__((always_inline)) {  // of the tile set_tile has chosen
 #pragma unroll
         for (int qb = 0; qb < kQB; ++qb) {  // rows past N read row N-1
             const int t = min(t0 + 32 * qb, N - 1);
@@ -114,14 +128,9 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
             for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
             cq[qb] = ch[t] - cbase;
         }
-        // key tiles that intersect the band of this query tile (window-aware pruning of Alg. 2)
-        const int k_lo = max(0, q0 - w + 1);
-        const int k_hi = min(N, q0 + BR) - 1;
-        j_lo = k_lo / kTileRows;
-        j_hi = k_hi / kTileRows;
-        ntiles = j_hi - j_lo + 1;
     };
     set_tile(tile);
+    load_queries();
     // ring slots that were never loaded are read by the first and last iterations of a band (as operands
     // of products with zero probabilities, or into scores that the mask overrides): make them finite once
     for (int o16 = tid * 16; o16 < (int)(offsetof(FwdSmem<D>, craw)); o16 += kFwdThreads * 16)
@@ -448,6 +457,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
         store_acc_rows<DB>(o[qb], inv, sm.v[0] + 4096 * wv, O + head_done + (size_t)row0 * D, N - row0, lane);
     }
     if (!more) break;
+    load_queries();  // after the stores: the fragments would otherwise be live beside the accumulators
     start_tile();
     }
 }

@@ -140,6 +140,7 @@ __device__ __forceinline__ void acc_init_rows(f32x16& acc, const float* vec, int
 template <int DB>
 __device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f, char* stage, bf16_t* g0,
                                                int rows_valid, int lane) {
+    GFWA_PIN(lane);  // the addresses below are derived here, not hoisted into registers that live across the caller's loops
     const int lk = lane & 31, h = lane >> 5;
     char* wr = stage + lk * 128 + 8 * h;
     const int wsw = (lk >> 1) & 7;
