@@ -227,11 +227,15 @@ const char *gfwa_profile_kernel_name(int k);
  * gfwa_probe_mfma runs a loop of `iterations` x 16 bf16 32x32x16 MFMAs per wave on `workgroups`
  * workgroups of 8 waves (two per SIMD; use a multiple of the number of compute units) and writes
  * the floating-point operations of the launch to *flops (host memory, may be NULL); `sink` is one
- * device float the kernel may write (it never does for these operands).  gfwa_probe_copy copies
+ * device float the kernel may write.  random_operands = 0: one pair of operand registers with small
+ * constant values (the rate at the highest clock the part reaches with busy matrix cores);
+ * nonzero: sixteen pairs of pseudo-random unit-variance operands, as the attention inputs are (the
+ * rate at the clock the part sustains when operands switch as on real data).  gfwa_probe_copy copies
  * `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned) with plain 16-byte accesses:
  * 2 * bytes of memory traffic.  Both only enqueue; the caller times them on its stream.
  */
-int gfwa_probe_mfma(float *sink, int iterations, int workgroups, double *flops, gfwa_stream_t stream);
+int gfwa_probe_mfma(float *sink, int iterations, int workgroups, int random_operands, double *flops,
+                    gfwa_stream_t stream);
 int gfwa_probe_copy(const void *src, void *dst, size_t bytes, gfwa_stream_t stream);
 
 #ifdef __cplusplus

@@ -75,7 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.gfwa_gate_scan_workspace_bytes.restype = ctypes.c_size_t
     lib.gfwa_gate_prefix_stp.argtypes = [fp, fp, f, fp, vp, ctypes.c_size_t, i, i, i, vp]
     lib.gfwa_gate_prefix_stp.restype = i
-    lib.gfwa_probe_mfma.argtypes = [fp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    lib.gfwa_probe_mfma.argtypes = [fp, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
     lib.gfwa_probe_mfma.restype = i
     lib.gfwa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.gfwa_probe_copy.restype = i
@@ -410,11 +410,13 @@ def gfwa_decode_static(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: t
     return o, L
 
 
-def gfwa_probe_mfma(sink: torch.Tensor, iterations: int, workgroups: int) -> float:
-    """Enqueue the pure bf16 MFMA loop; returns the floating-point operations of the launch."""
+def gfwa_probe_mfma(sink: torch.Tensor, iterations: int, workgroups: int, random_operands: bool = False) -> float:
+    """Enqueue the pure bf16 MFMA loop (constant or pseudo-random operands); returns the floating-point
+    operations of the launch."""
     _need(sink, tuple(sink.shape), torch.float32, "sink")
     flops = ctypes.c_double(0.0)
-    _check(load_library().gfwa_probe_mfma(sink.data_ptr(), int(iterations), int(workgroups), ctypes.byref(flops),
+    _check(load_library().gfwa_probe_mfma(sink.data_ptr(), int(iterations), int(workgroups), int(bool(random_operands)),
+                                          ctypes.byref(flops),
                                           _stream()))
     return float(flops.value)
 

@@ -253,11 +253,12 @@ const char* gfwa_strerror(int code) {
 
 int gfwa_version(void) { return 100; }
 
-int gfwa_probe_mfma(float* sink, int iterations, int workgroups, double* flops, gfwa_stream_t stream) {
+int gfwa_probe_mfma(float* sink, int iterations, int workgroups, int random_operands, double* flops,
+                    gfwa_stream_t stream) {
     if (!sink) return GFWA_ERR_NULL;
     if (iterations < 1 || workgroups < 1 || workgroups > (1 << 20) || iterations > (1 << 24)) return GFWA_ERR_DIM;
     if (!aligned(sink, 4)) return GFWA_ERR_ALIGN;
-    return hip_status(probe_mfma(sink, iterations, workgroups, flops, stream));
+    return hip_status(probe_mfma(sink, iterations, workgroups, random_operands != 0, flops, stream));
 }
 
 int gfwa_probe_copy(const void* src, void* dst, size_t bytes, gfwa_stream_t stream) {

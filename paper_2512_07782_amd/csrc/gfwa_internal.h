@@ -52,7 +52,7 @@ constexpr size_t kDecodeStaticBytes = (size_t)32 << 20;
 hipError_t decode_static_scratch(float** ptr);
 
 // Calibration kernels (probe.hip): a pure bf16 MFMA loop and a plain 16-byte copy.
-hipError_t probe_mfma(float* sink, int iterations, int workgroups, double* flops, hipStream_t s);
+hipError_t probe_mfma(float* sink, int iterations, int workgroups, int random_operands, double* flops, hipStream_t s);
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 // Kernel ids for the optional per-kernel event timing (see gfwa_profile_* in include/gfwa.h).

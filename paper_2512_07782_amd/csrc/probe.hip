@@ -12,27 +12,45 @@ namespace gfwa {
 constexpr int kProbeThreads = 512;  // 8 waves: two per SIMD
 constexpr int kProbeUnroll = 16;    // MFMAs per loop iteration and wave
 
+// RANDOM = false: one pair of operands with small constant values (few bits toggle: the rate at the highest clock
+// the part reaches with busy matrix cores).  RANDOM = true: sixteen pairs of pseudo-random operands of unit variance,
+// like the attention inputs, a different pair for every MFMA of the loop body (the rate at the clock the part
+// sustains when the operand buses and multipliers switch as they do on real data).
+template <bool RANDOM>
 __global__ __launch_bounds__(kProbeThreads) void probe_mfma_kernel(float* __restrict__ sink, int iterations) {
+    constexpr int NOP = RANDOM ? 4 : 1;
     f32x16 acc[4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
-    bf16x8 x, y;
+    bf16x8 x[NOP], y[NOP];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        x[e] = (bf16_t)(0.001f * (float)((threadIdx.x + e) & 31));
-        y[e] = (bf16_t)(0.002f * (float)((threadIdx.x + 3 * e) & 15));
-    }
+    for (int k = 0; k < NOP; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (RANDOM) {
+                // integer hash of (thread, workgroup, operand, element) -> uniform on [-sqrt 3, sqrt 3)
+                unsigned u = (threadIdx.x * 8u + e) * 2654435761u + (blockIdx.x * 4u + k) * 2246822519u + 374761393u;
+                u ^= u >> 15; u *= 2246822519u; u ^= u >> 13; u *= 3266489917u; u ^= u >> 16;
+                unsigned t = u * 2654435761u + 0x9e3779b9u;
+                t ^= t >> 15; t *= 2246822519u; t ^= t >> 13;
+                x[k][e] = (bf16_t)(((float)(u >> 8) * (1.0f / 8388608.0f) - 1.0f) * 1.7320508f);
+                y[k][e] = (bf16_t)(((float)(t >> 8) * (1.0f / 8388608.0f) - 1.0f) * 1.7320508f);
+            } else {
+                x[k][e] = (bf16_t)(0.001f * (float)((threadIdx.x + e) & 31));
+                y[k][e] = (bf16_t)(0.002f * (float)((threadIdx.x + 3 * e) & 15));
+            }
+        }
     for (int it = 0; it < iterations; ++it)
 #pragma unroll
-        for (int i = 0; i < kProbeUnroll; ++i) acc[i % 4] = mfma32(x, y, acc[i % 4]);
+        for (int i = 0; i < kProbeUnroll; ++i) acc[i % 4] = mfma32(x[i % NOP], y[(i / 4) % NOP], acc[i % 4]);
     float s = 0.f;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s += acc[a][v];
-    if (s == -1.0f) sink[0] = s;  // never true (all terms are >= 0): keeps the loop alive without a store
+    if (s == -1.0f) sink[0] = s;  // practically never true: keeps the loop alive without a store (sink is one float the caller owns)
 }
 
 __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
@@ -42,8 +60,11 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict
 
 // Launches the MFMA loop on `workgroups` workgroups of 8 waves; *flops receives the floating-point operations
 // the launch performs (2 * 32 * 32 * 16 per MFMA).
-hipError_t probe_mfma(float* sink, int iterations, int workgroups, double* flops, hipStream_t s) {
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, s, sink, iterations);
+hipError_t probe_mfma(float* sink, int iterations, int workgroups, int random_operands, double* flops, hipStream_t s) {
+    if (random_operands)
+        hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(workgroups), dim3(kProbeThreads), 0, s, sink, iterations);
+    else
+        hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(workgroups), dim3(kProbeThreads), 0, s, sink, iterations);
     if (flops) *flops = 2.0 * 32 * 32 * 16 * kProbeUnroll * (double)iterations * (kProbeThreads / 64) * (double)workgroups;
     return hipGetLastError();
 }

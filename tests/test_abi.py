@@ -96,8 +96,8 @@ def test_argument_validation_on_host(lib):
     assert lib.gfwa_decode_workspace_bytes(4096, 4, 8192, 128, 8192) > 32 << 20
     assert lib.gfwa_decode_static(*decs(B=4096, T=8192, w=8192)) == -5
     # calibration kernels
-    assert lib.gfwa_probe_mfma(None, 10, 256, None, None) == -1
-    assert lib.gfwa_probe_mfma(good, 0, 256, None, None) == -2
+    assert lib.gfwa_probe_mfma(None, 10, 256, 0, None, None) == -1
+    assert lib.gfwa_probe_mfma(good, 0, 256, 1, None, None) == -2
     assert lib.gfwa_probe_copy(good, None, 1024, None) == -1
     assert lib.gfwa_probe_copy(good, good, 1000, None) == -2
     assert lib.gfwa_probe_copy(odd, good, 1024, None) == -4
