@@ -229,8 +229,10 @@ const char *gfwa_profile_kernel_name(int k);
  * the floating-point operations of the launch to *flops (host memory, may be NULL); `sink` is one
  * device float the kernel may write.  random_operands = 0: one pair of operand registers with small
  * constant values (the rate at the highest clock the part reaches with busy matrix cores);
- * nonzero: sixteen pairs of pseudo-random unit-variance operands, as the attention inputs are (the
- * rate at the clock the part sustains when operands switch as on real data).  gfwa_probe_copy copies
+ * 1: sixteen pairs of pseudo-random unit-variance operands, as the attention inputs are (the rate at
+ * the clock the part sustains when operands switch as on real data); 2: the same with the least
+ * companion work an attention inner loop has per MFMA (one operand fragment read from LDS, four
+ * fused multiply-adds and one exp2 on the vector unit); other values: GFWA_ERR_DIM.  gfwa_probe_copy copies
  * `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned) with plain 16-byte accesses:
  * 2 * bytes of memory traffic.  Both only enqueue; the caller times them on its stream.
  */

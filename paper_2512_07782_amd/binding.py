@@ -410,12 +410,13 @@ def gfwa_decode_static(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, c: t
     return o, L
 
 
-def gfwa_probe_mfma(sink: torch.Tensor, iterations: int, workgroups: int, random_operands: bool = False) -> float:
-    """Enqueue the pure bf16 MFMA loop (constant or pseudo-random operands); returns the floating-point
-    operations of the launch."""
+def gfwa_probe_mfma(sink: torch.Tensor, iterations: int, workgroups: int, random_operands: int = 0) -> float:
+    """Enqueue the bf16 MFMA loop (0: constant operands, 1: pseudo-random operands, 2: pseudo-random operands
+    plus one LDS fragment read and five vector instructions per MFMA); returns the floating-point operations
+    of the launch."""
     _need(sink, tuple(sink.shape), torch.float32, "sink")
     flops = ctypes.c_double(0.0)
-    _check(load_library().gfwa_probe_mfma(sink.data_ptr(), int(iterations), int(workgroups), int(bool(random_operands)),
+    _check(load_library().gfwa_probe_mfma(sink.data_ptr(), int(iterations), int(workgroups), int(random_operands),
                                           ctypes.byref(flops),
                                           _stream()))
     return float(flops.value)

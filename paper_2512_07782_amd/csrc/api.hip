@@ -258,7 +258,8 @@ int gfwa_probe_mfma(float* sink, int iterations, int workgroups, int random_oper
     if (!sink) return GFWA_ERR_NULL;
     if (iterations < 1 || workgroups < 1 || workgroups > (1 << 20) || iterations > (1 << 24)) return GFWA_ERR_DIM;
     if (!aligned(sink, 4)) return GFWA_ERR_ALIGN;
-    return hip_status(probe_mfma(sink, iterations, workgroups, random_operands != 0, flops, stream));
+    if (random_operands < 0 || random_operands > 2) return GFWA_ERR_DIM;
+    return hip_status(probe_mfma(sink, iterations, workgroups, random_operands, flops, stream));
 }
 
 int gfwa_probe_copy(const void* src, void* dst, size_t bytes, gfwa_stream_t stream) {
