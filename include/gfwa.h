@@ -29,10 +29,13 @@ extern "C" {
 
 typedef struct ihipStream_t *gfwa_stream_t;
 
-typedef enum {
+/* Storage type of the matrices.  A plain int at the boundary (any value may arrive from a caller; the
+ * entry points answer GFWA_ERR_UNSUPPORTED to those that are not listed here). */
+typedef int gfwa_dtype_t;
+enum {
     GFWA_BF16 = 0, /* Q,K,V,O,dO,dQ,dK,dV stored as bfloat16; products on bf16 MFMA, fp32 accumulate */
     GFWA_F32 = 1   /* stored as float; all arithmetic fp32 */
-} gfwa_dtype_t;
+};
 
 typedef enum {
     GFWA_OK = 0,

@@ -21,7 +21,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gfwa_oracle.c")
-_LIB = os.path.join(_HERE, "libgfwa_oracle.so")
+# GFWA_ORACLE_LIB names another build of gfwa_oracle.c (a sanitizer build, for one); it is loaded as it is
+_LIB = os.environ.get("GFWA_ORACLE_LIB") or os.path.join(_HERE, "libgfwa_oracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
 _dp = ctypes.POINTER(ctypes.c_double)
@@ -29,6 +30,8 @@ _dp = ctypes.POINTER(ctypes.c_double)
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (fp64, OpenMP, no fast-math)."""
+    if os.environ.get("GFWA_ORACLE_LIB"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]

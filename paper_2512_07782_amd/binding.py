@@ -13,7 +13,8 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libgfwa.so")
+# GFWA_LIB names another build of the same library (a host-sanitizer build, for one)
+_LIB_PATH = os.environ.get("GFWA_LIB") or os.path.join(_HERE, "libgfwa.so")
 _lib: Optional[ctypes.CDLL] = None
 
 GFWA_BF16, GFWA_F32 = 0, 1
