@@ -136,7 +136,9 @@ __device__ __forceinline__ void acc_init_rows(f32x16& acc, const float* vec, int
 // the memory pipeline takes such an instruction one line at a time.  The block passes through `stage`, 4 KB
 // of LDS private to the wave, 64 columns at a time: 8-byte writes in accumulator order, 16-byte reads in row
 // order (16-byte chunks XOR-swizzled by row pair, two-way conflicts on the writes, none on the reads).
-// g0 = row 0, column 0 of the block; rows at or beyond rows_valid are not stored.
+// g0 = row 0, column 0 of the block; rows at or beyond rows_valid are not stored.  The stores are non-temporal: an
+// output is written once and read by a later kernel at the earliest, and should not push K, V, Q or dO tiles that
+// neighbouring workgroups are about to re-read out of the L2.
 template <int DB>
 __device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f, char* stage, bf16_t* g0,
                                                int rows_valid, int lane) {
@@ -159,7 +161,7 @@ __device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f,
         for (int i = 0; i < 4; ++i) {
             const int r = 8 * i + (lane >> 3), q = lane & 7;
             const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + r * 128 + ((q ^ ((r >> 1) & 7)) * 16));
-            if (r < rows_valid) *reinterpret_cast<bf16x8*>(g0 + (size_t)r * (32 * DB) + 64 * hf + 8 * q) = v;
+            if (r < rows_valid) __builtin_nontemporal_store(v, reinterpret_cast<bf16x8*>(g0 + (size_t)r * (32 * DB) + 64 * hf + 8 * q));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next 64 columns overwrite the stage
     }
