@@ -222,6 +222,46 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what this device sustains: bf16 MFMA loops on every SIMD, and a plain 1 GiB copy.  Run before the warm-up
+    # steps: about a third of a second of load, after which the part's clocks have settled, so that a short run
+    # (few warm-up and timed steps) measures the same state as a long one
+    achievable = None
+    if not args.no_peak_probe:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        best = {0: 0.0, 1: 0.0, 2: 0.0}
+        for random_operands in (0, 1, 2):
+            for rep in range(4):   # the first repetition also settles the clock under this load
+                e0.record()
+                flops = g.gfwa_probe_mfma(sink, 40000, ncu, random_operands)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    best[random_operands] = max(best[random_operands], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        best_tf, best_tf_random, best_tf_mix = best[0], best[1], best[2]
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        best_gb = 0.0
+        for rep in range(4):
+            e0.record()
+            nbytes = g.gfwa_probe_copy(src, dst)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best_gb = max(best_gb, 2.0 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        del src, dst
+        achievable = {"mfma_bf16_tflops": round(best_tf, 1), "mfma_frac_of_published": round(best_tf / PEAK_BF16_TFLOPS, 4),
+                      "mfma_bf16_tflops_random_operands": round(best_tf_random, 1),
+                      "mfma_random_frac_of_published": round(best_tf_random / PEAK_BF16_TFLOPS, 4),
+                      "mfma_bf16_tflops_attention_mix": round(best_tf_mix, 1),
+                      "mfma_mix_frac_of_published": round(best_tf_mix / PEAK_BF16_TFLOPS, 4),
+                      "copy_gbs": round(best_gb, 1), "copy_frac_of_published": round(best_gb / PEAK_HBM_GBS, 4),
+                      "how": "gfwa_probe_mfma: 40000 x 16 MFMAs per wave, 8 waves on every CU, best of 3, once with one "
+                             "constant operand pair, once with sixteen pseudo-random unit-variance pairs (the clock "
+                             "the part sustains depends on how much the operands switch), once with those and one LDS "
+                             "fragment read, four fma and one exp2 per MFMA (the least an attention inner loop does); "
+                             "gfwa_probe_copy: 1 GiB read + 1 GiB written, best of 3"}
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -262,44 +302,6 @@ def main() -> int:
     }
     if wl.backward:
         call_ms["backward"] = stats([m[2].elapsed_time(m[3]) for m in marks])
-
-    # ---- what this device sustains: a pure bf16 MFMA loop on every SIMD, and a plain 1 GiB copy
-    achievable = None
-    if not args.no_peak_probe:
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        sink = torch.zeros(1, dtype=torch.float32, device=dev)
-        best = {0: 0.0, 1: 0.0, 2: 0.0}
-        for random_operands in (0, 1, 2):
-            for rep in range(4):   # the first repetition also settles the clock under this load
-                e0.record()
-                flops = g.gfwa_probe_mfma(sink, 40000, ncu, random_operands)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep:
-                    best[random_operands] = max(best[random_operands], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-        best_tf, best_tf_random, best_tf_mix = best[0], best[1], best[2]
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        best_gb = 0.0
-        for rep in range(4):
-            e0.record()
-            nbytes = g.gfwa_probe_copy(src, dst)
-            e1.record()
-            torch.cuda.synchronize()
-            if rep:
-                best_gb = max(best_gb, 2.0 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-        del src, dst
-        achievable = {"mfma_bf16_tflops": round(best_tf, 1), "mfma_frac_of_published": round(best_tf / PEAK_BF16_TFLOPS, 4),
-                      "mfma_bf16_tflops_random_operands": round(best_tf_random, 1),
-                      "mfma_random_frac_of_published": round(best_tf_random / PEAK_BF16_TFLOPS, 4),
-                      "mfma_bf16_tflops_attention_mix": round(best_tf_mix, 1),
-                      "mfma_mix_frac_of_published": round(best_tf_mix / PEAK_BF16_TFLOPS, 4),
-                      "copy_gbs": round(best_gb, 1), "copy_frac_of_published": round(best_gb / PEAK_HBM_GBS, 4),
-                      "how": "gfwa_probe_mfma: 40000 x 16 MFMAs per wave, 8 waves on every CU, best of 3, once with one "
-                             "constant operand pair, once with sixteen pseudo-random unit-variance pairs (the clock "
-                             "the part sustains depends on how much the operands switch), once with those and one LDS "
-                             "fragment read, four fma and one exp2 per MFMA (the least an attention inner loop does); "
-                             "gfwa_probe_copy: 1 GiB read + 1 GiB written, best of 3"}
 
     f_fwd = wl.flops_fwd_nominal()
     f_bwd = wl.flops_bwd_nominal() if wl.backward else 0.0
