@@ -64,12 +64,16 @@ constexpr int kQueryBlocks = 1;
 template <int D>
 constexpr int kFwdBR = 32 * kQueryBlocks<D> * kFwdWaves;  // queries per workgroup
 constexpr int kRing = 2;                         // K and V tile slots each: one being read, one in flight
+// Resident workgroups per CU: two at d = 128 (256 registers per wave); three at d = 64, where the accumulators are
+// half as large (the kernel fits 168 registers) and a workgroup's rings take 33 KB of LDS.
+template <int D>
+constexpr int kFwdResident = D == 64 ? 3 : 2;
 
 template <int D>
 using FwdSmem = KvRingSmem<D, kRing>;
 
 template <int D>
-__global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(
+__global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ c, bf16_t* __restrict__ O, float* __restrict__ L, int N, int w,
     float scale_log2, int num_qtiles, int total_tiles, int H, int G) {
@@ -472,7 +476,7 @@ static hipError_t launch_fwd(const void* Q, const void* K, const void* V, const 
                                          lds_allowed))
         return e;
     const int num_cu = device_cu_count();
-    const int grid = total < 2 * num_cu ? total : 2 * num_cu;  // two resident workgroups per CU
+    const int grid = total < kFwdResident<D> * num_cu ? total : kFwdResident<D> * num_cu;  // every workgroup resident
     ProfScope prof(kKernForward, s);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), dim3(grid), dim3(kFwdThreads), sizeof(FwdSmem<D>), s,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, c, (bf16_t*)O, L, N, w,
