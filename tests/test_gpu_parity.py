@@ -502,7 +502,8 @@ SMALL_BWD = [(1, 1, 1, 64, 1), (1, 2, 37, 64, 5), (2, 1, 129, 128, 1), (1, 2, 30
 TINY_BWD = [(1, 1, 2, 128, 34, 0.5, 29), (1, 1, 2, 64, 2, 0.5, 31), (1, 2, 2, 128, 2, -1.0, 12), (1, 1, 3, 64, 3, -1.0, 12),
             (2, 1, 4, 128, 2, -1.0, 12), (1, 1, 5, 64, 100, -1.0, 12), (1, 2, 8, 128, 3, -1.0, 12),
             (1, 1, 16, 64, 16, -1.0, 12), (1, 1, 31, 128, 7, -1.0, 12), (1, 2, 33, 128, 32, -1.0, 12),
-            (1, 1, 33, 64, 33, 0.5, 30)]
+            (1, 1, 33, 64, 33, 0.5, 30),
+            (1, 1, 6, 64, 322, 0.5, 28)]   # a later sweep's only case above 1e-2 against the exact gradient (dalpha 1.06e-2, 1.2e-6 against Alg. 3 on the stored O)
 
 
 @pytest.mark.parametrize("chained", [False, True])
