@@ -19,6 +19,7 @@ ROCm 7.2; counters are collected in runs of their own, without any trace option)
 and then, with the standard output of the first run saved as OUT/kt.log::
 
     python3 -m paper_2512_07782_amd.profile_summary kernel-trace OUT/kt OUT/kt.log  > profiles/bench_long_bwd_kernel_trace.txt
+    (other workloads: the same trace with bench.py's arguments as a fourth argument, e.g. "--workload train_bwd --no-cpu-baseline")
     python3 -m paper_2512_07782_amd.profile_summary hbm-traffic OUT/fetch OUT/write > profiles/hbm_traffic_long_bwd.txt
     python3 -m paper_2512_07782_amd.profile_summary sq-counters OUT/sqA OUT/sqB OUT/kt > profiles/sq_counters_long_bwd.txt
 
@@ -44,6 +45,13 @@ LIB = {
     "bwd_dq_spill_bf16_kernel<128>": "bwd_dq",
     "segment_sum_kernel<true, 1>": "gate_grad_segment_sum",
     "scan_rows_kernel<true, 1>": "gate_grad_scan",
+    # the other head dimension and the backward with its minimum workspace
+    "fwd_bf16_kernel<64>": "forward",
+    "rowdot_bf16_kernel<64>": "bwd_rowdot",
+    "bwd_dkv_bf16_kernel<64>": "bwd_dkv",
+    "bwd_dq_bf16_kernel<64>": "bwd_dq",
+    "bwd_dkv8_bf16_kernel<128, false>": "bwd_dkv",
+    "bwd_dq_bf16_kernel<128>": "bwd_dq",
 }
 # the long_bwd workload of bench.py
 B, H, N, D, W = 1, 32, 16384, 128, 1024
@@ -80,15 +88,15 @@ def bench_line(log: str) -> dict:
     return json.loads(lines[-1]), lines[-1].strip()
 
 
-def kernel_trace(kt_dir: str, log: str) -> str:
+def kernel_trace(kt_dir: str, log: str, bench_args: str = "--no-cpu-baseline") -> str:
     stats = one(os.path.join(kt_dir, "**", "*_kernel_stats.csv"))
     bj, raw = bench_line(log)
     out = [
-        "rocprofv3 kernel trace of bench.py, workload long_bwd (B=1 H=32 N=16384 d=128 w=1024 bf16;",
-        "one step = gate prefix scan + forward + backward), one MI355X.",
+        f"rocprofv3 kernel trace of bench.py, workload {bj['config']['workload']}",
+        "(one step = gate prefix scan + forward + backward if the workload has one), one MI355X.",
         "",
         "command (from the repository root; rocprofv3 of ROCm 7.2):",
-        "  rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- python3 bench.py --no-cpu-baseline",
+        f"  rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- python3 bench.py {bench_args}",
         f"      (bench.py defaults: {bj['warmup']} warm-up + {bj['steps']} timed steps, then the same steps once more with an event",
         "       between the calls, then the calibration loops)",
         "summary made by: python3 -m paper_2512_07782_amd.profile_summary kernel-trace OUT/kt OUT/kt.log",
@@ -238,7 +246,7 @@ def sq_counters(a_dir: str, b_dir: str, kt_dir: str) -> str:
 
 def main(argv: list[str]) -> int:
     if len(argv) >= 4 and argv[1] == "kernel-trace":
-        sys.stdout.write(kernel_trace(argv[2], argv[3]))
+        sys.stdout.write(kernel_trace(argv[2], argv[3], *argv[4:5]))
     elif len(argv) >= 4 and argv[1] == "hbm-traffic":
         sys.stdout.write(hbm_traffic(argv[2], argv[3]))
     elif len(argv) >= 5 and argv[1] == "sq-counters":

@@ -43,7 +43,7 @@ def test_kernel_trace_and_sq_counters(tmp_path):
         w.writerow([K["dkv"], 10, 6800000, 680000.0, 40.0, 670000, 690000, 1.0])
         w.writerow([K["dq"], 10, 2600000, 260000.0, 10.0, 250000, 270000, 1.0])
     log = tmp_path / "kt.log"
-    log.write_text("noise\n" + json.dumps({"steps": 5, "warmup": 1, "kernels": {"forward": {"avg_ms": 0.341}}}) + "\n")
+    log.write_text("noise\n" + json.dumps({"steps": 5, "warmup": 1, "config": {"workload": "test"}, "kernels": {"forward": {"avg_ms": 0.341}}}) + "\n")
     text = ps.kernel_trace(str(kt), str(log))
     row = [l for l in text.splitlines() if l.startswith("fwd_bf16_kernel<128>")][0].split()
     assert row[-1] == "341.0" and "340.0" in row
