@@ -483,10 +483,14 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                 if (SPILL) {
                     // the column sums take the rounded values the dQ kernel will sum along the rows, so that
                     // the two cancel exactly in the suffix sums of the gate gradient; then the block is stored
+                    // (two values per instruction through the bf16 dot product with ones: a quarter of the vector
+                    // instructions of convert-and-add, and in this phase no MFMA of this wave is waiting behind it)
+                    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) colsum += (float)dsf[c2][e];
+                        for (int e = 0; e < 8; e += 2)
+                            colsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{dsf[c2][e], dsf[c2][e + 1]}, ones, colsum, false);
                     const int qb = 2 * i + sb, kb = kw0 >> 5;
                     char* blk = ds_ws + (((size_t)bh * nqb + qb) * nslot + (kb - qb + nslot - 1)) * kSpillBlockBytes;
                     // streaming stores: the blocks are read once, by the next kernel, and must not push the
@@ -881,10 +885,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_spill_bf16_kernel(
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
                     dq_acc[db] = mfma32(lds_read_tr_frag<D>(kt, 32 * sb + 16 * cc, db, lane), dsf[cc], dq_acc[db]);
+            // (pairs through the bf16 dot-product instruction, as the dK/dV kernel sums the same values along the columns)
+            const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) rowsum += (float)dsf[cc][e];
+                for (int e = 0; e < 8; e += 2)
+                    rowsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{dsf[cc][e], dsf[cc][e + 1]}, ones, rowsum, false);
         }
         __builtin_amdgcn_s_waitcnt(vmcnt_only(0));  // this wave's loads of tile j+1 have landed
         __syncthreads();
