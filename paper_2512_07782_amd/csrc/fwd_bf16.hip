@@ -20,8 +20,8 @@
 //   matrix pipe:  S(n) = g + K Q^T      and      O += V^T P(n-2)          (16 MFMAs at d = 128)
 //   vector unit:  P(n-1) = exp2(S(n-1) * sl - m * sl), row sums
 //   LDS:          the fragments of the MFMAs four steps ahead
-//   load unit:    this wave's share of the keys of tile T+1 (first block of a tile) or of the values of
-//                 tile T (second block), in two groups between the MFMAs
+//   load unit:    in the first block of a tile, this wave's share of the keys of tile T+1 and of the values of
+//                 tile T, in three groups between the MFMAs (both target slots are idle from the start of the step)
 // Nothing in an iteration depends on anything else in it, so the MFMAs issue back to back while the
 // exponentials of the previous block and the fragment reads of the next MFMAs fill the issue slots
 // between them (an MFMA occupies the matrix pipe for 32 cycles; about five vector and two LDS
@@ -29,7 +29,8 @@
 // step hands the ring slots over.  The V tile of step T is requested in step T and first read in step
 // T+1 (by the PV products, which lag two blocks), the K tile of step T+1 is requested in step T.
 // When a tile is finished the first key tile of the next one is requested before O is stored, and O
-// leaves as whole 128-byte lines through the idle V ring.
+// leaves as whole 128-byte lines through the idle V ring.  The next tile's queries arrive through the rings as
+// well when the tile count is even (d = 128): the last step's loads, which no product reads, fetch them.
 //
 // The gate bias rides in the MFMA accumulator: S is initialised with g_i = (c_i - c_base) / scale
 // straight from LDS before the K Q^T chain, so S = q.k + g_i and the probability is one fused
@@ -123,18 +124,40 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
         j_hi = k_hi / kTileRows;
         ntiles = j_hi - j_lo + 1;
     };
-    auto load_queries = [&]() __attribute__((always_inline)) {  // of the tile set_tile has chosen
+    // The queries of the next tile can travel through the rings: the last step of a tile (the drain step, T = ntiles)
+    // still issues a load of K tile ntiles + 1 and of V tile ntiles, which nothing reads; when the tile count is even
+    // those land in K slot 1 and V slot 0, both idle by then, and the first key tile of the next query tile goes to
+    // K slot 0.  So in that step the two loads fetch the next tile's 128 queries instead (first 64 into the K slot,
+    // last 64 into the V slot, swizzled like any tile), and the waves pick their Q fragments up from LDS when the tile
+    // starts instead of waiting for a round trip to memory.  (d = 128 only: at d = 64 the output staging needs both
+    // V slots.  Odd tile counts keep the loads from global memory.)
+    constexpr bool kStageQ = D == 128 && kQB == 1;
+    int stage_T = -1000;      // the step whose spare loads fetch the next tile's queries, if any
+    const char* Qn = nullptr; // Q of the next tile's head
+    int qn0 = 0;              // first query of the next tile
+    auto plan_next = [&]() __attribute__((always_inline)) {
+        const int tn = tile_of(wg_step + 1);
+        const bool ok = kStageQ && tn < total_tiles && (ntiles & 1) == 0;
+        stage_T = ok ? ntiles : -1000;
+        qn0 = (tn % num_qtiles) * BR;
+        Qn = reinterpret_cast<const char*>(Q + (size_t)(tn / num_qtiles) * N * D);
+    };
+    auto load_query_gates = [&]() __attribute__((always_inline)) {  // c_t - c_base of the tile set_tile has chosen (rows past N read row N-1)
 #pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) {  // rows past N read row N-1
+        for (int qb = 0; qb < kQB; ++qb) cq[qb] = ch[min(t0 + 32 * qb, N - 1)] - cbase;
+    };
+    auto load_queries = [&]() __attribute__((always_inline)) {  // Q fragments of that tile, from global memory
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
             const int t = min(t0 + 32 * qb, N - 1);
             const bf16_t* qp = Q + head_off + (size_t)t * D + 8 * h;
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
-            cq[qb] = ch[t] - cbase;
         }
     };
     set_tile(tile);
     load_queries();
+    load_query_gates();
     // ring slots that were never loaded are read by the first and last iterations of a band (as operands
     // of products with zero probabilities, or into scores that the mask overrides): make them finite once
     for (int o16 = tid * 16; o16 < (int)(offsetof(FwdSmem<D>, craw)); o16 += kFwdThreads * 16)
@@ -154,11 +177,15 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
     const int ld_row0 = kRowsPerWave * wv + lane / kChunksPerRow;
     const unsigned ld_chunk0 = (unsigned)(swz_chunk<D>(ld_row0, lane % kChunksPerRow) * 16);
     // load g of tile T (position in visiting order: tile j_hi - T) of the matrix at Mh into its ring slot
-    auto load_piece = [&](const char* Mh, char (&ring)[kRing][kTileRows * D * 2], int T, int g) __attribute__((always_inline)) {
+    // (is_v: the V ring; the spare loads of the drain step fetch the next tile's queries, see plan_next)
+    auto load_piece = [&](const char* Mh, char (&ring)[kRing][kTileRows * D * 2], int T, int g, bool is_v) __attribute__((always_inline)) {
+        const bool spare = kStageQ && T == stage_T + (is_v ? 0 : 1);
         const int j = max(j_hi - T, 0);
-        const int row = min(j * kTileRows + kRowsPerLoad * g + ld_row0, N - 1);
+        const int row0 = spare ? qn0 + (is_v ? kTileRows : 0) : j * kTileRows;
+        const char* M = spare ? Qn : Mh;
+        const int row = min(row0 + kRowsPerLoad * g + ld_row0, N - 1);
         const unsigned chunk = ld_chunk0 ^ (unsigned)((swz_chunk<D>(kRowsPerLoad * g, 0)) * 16);
-        dma16(Mh, (unsigned)row * (unsigned)(D * 2) + chunk, ring[T % kRing] + (kRowsPerWave * wv + kRowsPerLoad * g) * (D * 2));
+        dma16(M, (unsigned)row * (unsigned)(D * 2) + chunk, ring[T % kRing] + (kRowsPerWave * wv + kRowsPerLoad * g) * (D * 2));
     };
     auto load_gate = [&](int T) __attribute__((always_inline)) {  // the 64 gate values of tile T's keys (every wave, same place)
         const int j = max(j_hi - T, 0);
@@ -167,11 +194,11 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
     auto issue_k = [&](int T) __attribute__((always_inline)) {  // keys of tile T and their gate values
         load_gate(T);
 #pragma unroll
-        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Kh, sm.k, T, g);
+        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Kh, sm.k, T, g, false);
     };
     auto issue_v = [&](int T) __attribute__((always_inline)) {
 #pragma unroll
-        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Vh, sm.v, T, g);
+        for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Vh, sm.v, T, g, true);
     };
     auto publish_gate = [&](int T) __attribute__((always_inline)) {  // wave 0: raw c it loaded itself -> accumulator initial values
         const int buf = T % kRing;
@@ -341,16 +368,17 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
             }
             // this wave's share of the step's tile loads, spread between the MFMAs so that the load unit's
             // queue never fills: block 0 issues the keys of tile T+1 (and their gate values), block 1 the values of tile T
-            if (i == NF / 3 || i == 2 * NF / 3) {  // in two groups (inline assembly the scheduler cannot move work across)
-                const int g0 = i == NF / 3 ? 0 : kLoadsPerWave / 2, g1 = i == NF / 3 ? kLoadsPerWave / 2 : kLoadsPerWave;
+            if (b == 0 && (i == NF / 4 || i == NF / 2 || i == 3 * NF / 4)) {  // in groups (inline assembly the scheduler cannot move work across)
+                // the keys of tile T+1, their gate values and the values of tile T, all in the first block of the step:
+                // every slot they go to has been idle since the step began
+                if (i == NF / 4) {
+                    load_gate(T + 1);
 #pragma unroll
-                for (int g = g0; g < g1; ++g) {
-                    if (b == 0) {
-                        if (g == 0) load_gate(T + 1);
-                        load_piece(Kh, sm.k, T + 1, g);
-                    } else {
-                        load_piece(Vh, sm.v, T, g);
-                    }
+                    for (int g = 0; g < kLoadsPerWave; ++g) load_piece(Kh, sm.k, T + 1, g, false);
+                } else {
+                    const int g0 = i == NF / 2 ? 0 : kLoadsPerWave / 2, g1 = i == NF / 2 ? kLoadsPerWave / 2 : kLoadsPerWave;
+#pragma unroll
+                    for (int g = g0; g < g1; ++g) load_piece(Vh, sm.v, T, g, true);
                 }
             }
             // the softmax of block n-1: pairs [i kPairs / NF, (i + 1) kPairs / NF) in this step
@@ -416,6 +444,7 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
         n_first = block_of(khi);
         n_last = qw0 < N ? block_of(klo) : n_first - 3;
     }
+    plan_next();
     // T = ntiles is the drain step (softmax of the last block, PV products of the last tile)
     {
         // steps this wave computes in: T_first .. T_last (its blocks n_first .. n_last + 2); the others only load
@@ -448,6 +477,7 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
         tile = tile_of(++wg_step);
         set_tile(tile);
         open_tile();
+        load_query_gates();  // requested now, first used when the tile ends
     }
     // ---- epilogue: O = O^T / l, L = ln2 * (m*sl + log2 l) - (c_t - c_base)
 #pragma unroll
@@ -456,12 +486,21 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
         const int t = t_done + 32 * qb;
         const float inv = 1.0f / lt;
         if (t < N && h == 0) L[(size_t)bh_done * N + t] = (m[qb] * sl + fast_log2(lt)) * kLn2 - cq_done[qb];
-        // O as whole lines, through 4 KB per wave of the V ring (idle until the first step of the next tile)
+        // O as whole lines, through 4 KB per wave of the V ring (idle until the first step of the next tile; slot 0 may
+        // hold the second half of the next tile's queries, slot 1 is free in either case)
         const int row0 = t - lq;
-        store_acc_rows<DB>(o[qb], inv, sm.v[0] + 4096 * wv, O + head_done + (size_t)row0 * D, N - row0, lane);
+        store_acc_rows<DB>(o[qb], inv, sm.v[kStageQ ? 1 : 0] + 4096 * wv, O + head_done + (size_t)row0 * D, N - row0, lane);
     }
     if (!more) break;
-    load_queries();  // after the stores: the fragments would otherwise be live beside the accumulators
+    // the Q fragments, after the stores (they would otherwise be live beside the accumulators): from the rings if the
+    // drain step has fetched them (rows 32 wv .. of the 128: waves 0, 1 from K slot 1, waves 2, 3 from V slot 0)
+    if (kStageQ && stage_T >= 0) {
+        const int disp = (wv < 2 ? 1 : kRing) * kTileBytes + (wv & 1) * 32 * (D * 2);
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) qf[0][kc] = read_k(kc, disp);
+    } else {
+        load_queries();
+    }
     start_tile();
     }
 }
