@@ -347,7 +347,7 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
     // dS spill: 32-query blocks per head, slots per query block, this lane's 16-byte slot in the two pieces
     const int nqb = (N + 31) / 32;
     const int nslot = ds_spill_slots(w, nqb);
-    const int spill_lane0 = 16 * lane, spill_lane1 = 1024 + 16 * lane;
+    const int spill_lane0 = 16 * lane;  // (the second piece: + 1024, an immediate of its store)
 
     TilePairLoader<D, 8> loader;
     loader.init(wv, lane);
@@ -498,8 +498,8 @@ __global__ __launch_bounds__(2 * kThreads, 1) void bwd_dkv8_bf16_kernel(
                     // Written as instructions, not as stores the compiler may split, merge or move: the wait at the
                     // end of the tile is s_waitcnt vmcnt(2), which leaves exactly these two in flight and therefore
                     // counts on both having been issued after the tile's direct global->LDS loads and before it.
-                    stream_store16(blk + spill_lane0, dsf[0]);
-                    stream_store16(blk + spill_lane1, dsf[1]);
+                    stream_store16<0>(uniform_ptr(blk), (unsigned)spill_lane0, dsf[0]);
+                    stream_store16<1024>(uniform_ptr(blk), (unsigned)spill_lane0, dsf[1]);
                 }
                 if (D != 128) {
 #pragma unroll

@@ -138,10 +138,20 @@ __device__ __forceinline__ void dma4(const void* sbase, unsigned voff, const voi
         : "s"(lds_addr), "v"(voff), "s"(sbase)
         : "memory");
 }
-// One 16-byte non-temporal global store per lane, issued exactly here in program order (inline assembly with a
-// memory clobber): for code that counts its outstanding vector-memory operations by hand.
-__device__ __forceinline__ void stream_store16(void* p, bf16x8 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+// A pointer that is the same in every lane, moved into scalar registers (the first lane's value).
+__device__ __forceinline__ void* uniform_ptr(void* p) {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    return reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+}
+// One 16-byte non-temporal global store per lane to  sbase + voff + IMM, issued exactly here in program order (inline
+// assembly with a memory clobber): for code that counts its outstanding vector-memory operations by hand.  sbase
+// must be the same in every lane.  (Scalar base plus a 32-bit offset per lane: one address register instead of two.  In a
+// loop of nothing but MFMAs and such stores this form costs the wave 30 ns per store against 150 ns for the form with
+// a 64-bit address per lane; in the kernels here the two measure the same.)
+template <int IMM = 0>
+__device__ __forceinline__ void stream_store16(void* sbase, unsigned voff, bf16x8 v) {
+    asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3 nt" ::"v"(voff), "v"(v), "s"(sbase), "n"(IMM) : "memory");
 }
 // s_waitcnt that waits only for vmcnt <= n (gfx9 encoding: expcnt and lgkmcnt fields left at max)
 constexpr int vmcnt_only(int n) { return 0x0f70 | (n & 0xf) | ((n >> 4) << 14); }

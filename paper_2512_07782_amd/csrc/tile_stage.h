@@ -144,6 +144,7 @@ __device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f,
                                                int rows_valid, int lane) {
     GFWA_PIN(lane);  // the addresses below are derived here, not hoisted into registers that live across the caller's loops
     const int lk = lane & 31, h = lane >> 5;
+    void* gs = uniform_ptr(g0);  // the block's first row: the same in every lane
     char* wr = stage + lk * 128 + 8 * h;
     const int wsw = (lk >> 1) & 7;
 #pragma unroll
@@ -161,7 +162,7 @@ __device__ __forceinline__ void store_acc_rows(const f32x16 (&acc)[DB], float f,
         for (int i = 0; i < 4; ++i) {
             const int r = 8 * i + (lane >> 3), q = lane & 7;
             const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + r * 128 + ((q ^ ((r >> 1) & 7)) * 16));
-            if (r < rows_valid) __builtin_nontemporal_store(v, reinterpret_cast<bf16x8*>(g0 + (size_t)r * (32 * DB) + 64 * hf + 8 * q));
+            if (r < rows_valid) stream_store16<0>(gs, (unsigned)(r * (64 * DB) + 128 * hf + 16 * q), v);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next 64 columns overwrite the stage
     }
