@@ -222,42 +222,12 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- what this device sustains: bf16 MFMA loops on every SIMD, and a plain 1 GiB copy.  Run before the warm-up
-    # steps: about a third of a second of load, after which the part's clocks have settled, so that a short run
-    # (few warm-up and timed steps) measures the same state as a long one
+    # ---- what this device sustains: bf16 MFMA loops on every SIMD, and a plain 1 GiB copy.  Run first: about a third of
+    # a second of load (the copy first, the matrix-core loops last, so that what follows starts on a part under load)
     achievable = None
     if not args.no_peak_probe:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
-        # the copy first, the matrix-core loops last: the steps that follow start on a part that is under load
-        best = {0: 0.0, 1: 0.0, 2: 0.0}
-        for random_operands in (0, 1, 2):
-            for rep in range(4):   # the first repetition also settles the clock under this load
-                e0.record()
-                flops = g.gfwa_probe_mfma(sink, 40000, ncu, random_operands)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep:
-                    best[random_operands] = max(best[random_operands], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-        best_tf, best_tf_random, best_tf_mix = best[0], best[1], best[2]
-
-    # ---- what this device sustains: bf16 MFMA loops on every SIMD, and a plain 1 GiB copy.  Run before the warm-up
-    # steps: about a third of a second of load, after which the part's clocks have settled, so that a short run
-    # (few warm-up and timed steps) measures the same state as a long one
-    achievable = None
-    if not args.no_peak_probe:
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        sink = torch.zeros(1, dtype=torch.float32, device=dev)
-        best = {0: 0.0, 1: 0.0, 2: 0.0}
-        for random_operands in (0, 1, 2):
-            for rep in range(4):   # the first repetition also settles the clock under this load
-                e0.record()
-                flops = g.gfwa_probe_mfma(sink, 40000, ncu, random_operands)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep:
-                    best[random_operands] = max(best[random_operands], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-        best_tf, best_tf_random, best_tf_mix = best[0], best[1], best[2]
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         best_gb = 0.0
@@ -269,6 +239,16 @@ def main() -> int:
             if rep:
                 best_gb = max(best_gb, 2.0 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         del src, dst
+        best = {0: 0.0, 1: 0.0, 2: 0.0}
+        for random_operands in (0, 1, 2):
+            for rep in range(4):   # the first repetition also settles the clock under this load
+                e0.record()
+                flops = g.gfwa_probe_mfma(sink, 40000, ncu, random_operands)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    best[random_operands] = max(best[random_operands], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        best_tf, best_tf_random, best_tf_mix = best[0], best[1], best[2]
         achievable = {"mfma_bf16_tflops": round(best_tf, 1), "mfma_frac_of_published": round(best_tf / PEAK_BF16_TFLOPS, 4),
                       "mfma_bf16_tflops_random_operands": round(best_tf_random, 1),
                       "mfma_random_frac_of_published": round(best_tf_random / PEAK_BF16_TFLOPS, 4),

@@ -97,12 +97,13 @@ def kernel_trace(kt_dir: str, log: str, bench_args: str = "--no-cpu-baseline") -
         "",
         "command (from the repository root; rocprofv3 of ROCm 7.2):",
         f"  rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- python3 bench.py {bench_args}",
-        f"      (bench.py defaults: {bj['warmup']} warm-up + {bj['steps']} timed steps, then the same steps once more with an event",
-        "       between the calls, then the calibration loops)",
+        f"      (bench.py, in this order: the calibration loops, {bj['warmup']} + {bj['steps']} steps with an event between the calls,",
+        f"       {bj['warmup']} warm-up + {bj['steps']} timed steps)",
         "summary made by: python3 -m paper_2512_07782_amd.profile_summary kernel-trace OUT/kt OUT/kt.log",
         "",
-        "kernel_stats.csv (the warm-up steps, slower while the clocks settle, are in rocprofv3's average but not in",
-        "bench.py's), next to the average bench.py measured with HIP events around the same launches in the same run.",
+        "kernel_stats.csv (all launches of the run: the warm-up steps and the first steps after the calibration loops,",
+        "slower while the clocks settle, are in rocprofv3's average), next to the average bench.py measured with HIP",
+        "events around the launches of its breakdown pass in the same run.",
         "scan_rows_kernel<reverse, input> / segment_sum_kernel<reverse, input>: input 0 = one tensor, 1 = difference of two",
         "tensors.  probe_* are the calibration loops (matrix cores with constant / pseudo-random operands / attention mix, copy).",
         "",
