@@ -24,6 +24,85 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
 
 
+class BoardPower:
+    """Board power and shader clock of the GPU under test, read (never written) from the amdgpu driver's hwmon and
+    pp_dpm_sclk files while a load runs.  None of it is needed for the timing; absent files just give no figures."""
+
+    def __init__(self, torch):
+        import glob
+        self.power = self.cap = self.sclk = None
+        try:
+            p = torch.cuda.get_device_properties(0)
+            bus = f"{p.pci_domain_id:04x}:{p.pci_bus_id:02x}:{p.pci_device_id:02x}.0"
+        except Exception:
+            bus = ""
+        cards = sorted(glob.glob("/sys/class/drm/card[0-9]*/device"))
+        mine = [c for c in cards if bus and os.path.realpath(c).lower().endswith(bus)] or (cards if len(cards) == 1 else [])
+        for c in mine[:1]:
+            for hw in sorted(glob.glob(os.path.join(c, "hwmon", "hwmon*"))):
+                for name in ("power1_input", "power1_average"):
+                    if self.power is None and os.path.exists(os.path.join(hw, name)):
+                        self.power = os.path.join(hw, name)
+                if os.path.exists(os.path.join(hw, "power1_cap")):
+                    self.cap = os.path.join(hw, "power1_cap")
+            if os.path.exists(os.path.join(c, "pp_dpm_sclk")):
+                self.sclk = os.path.join(c, "pp_dpm_sclk")
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except OSError:
+            return None
+
+    def watts(self):
+        v = self._read(self.power) if self.power else None
+        return float(v) / 1e6 if v and v.strip().isdigit() else None
+
+    def cap_watts(self):
+        v = self._read(self.cap) if self.cap else None
+        return float(v) / 1e6 if v and v.strip().isdigit() else None
+
+    def sclk_mhz(self):
+        for line in (self._read(self.sclk) or "").splitlines() if self.sclk else ():
+            if line.rstrip().endswith("*"):
+                digits = "".join(ch for ch in line.split(":")[-1] if ch.isdigit())
+                return float(digits) if digits else None
+        return None
+
+    def during(self, torch, launch, seconds, settle=0.3):
+        """Run `launch` back to back for `seconds`; mean/max of the samples taken after the first `settle` seconds."""
+        import threading
+        if self.power is None:
+            return None
+        stop, samples = threading.Event(), []
+
+        def sampler():
+            while not stop.is_set():
+                samples.append((time.perf_counter(), self.watts(), self.sclk_mhz()))
+                stop.wait(0.02)
+        th = threading.Thread(target=sampler, daemon=True)
+        t0 = time.perf_counter()
+        th.start()
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(10):
+                launch()
+            torch.cuda.synchronize()
+            n += 10
+        t1 = time.perf_counter()
+        stop.set()
+        th.join()
+        w_ = [p for t, p, _ in samples if t - t0 >= settle and p is not None]
+        f_ = [f for t, _, f in samples if t - t0 >= settle and f is not None]
+        if not w_:
+            return None
+        return {"board_w_mean": round(sum(w_) / len(w_), 1), "board_w_max": round(max(w_), 1),
+                "sclk_mhz_mean": round(sum(f_) / len(f_), 0) if f_ else None, "samples": len(w_),
+                "launches": n, "ms_per_launch": round((t1 - t0) / n * 1e3, 4)}
+
+
 def gate_only(args, g, torch) -> int:
     """The memory-bound gate kernels alone, at a size that saturates HBM; algorithmic bytes as in main()
     (the scan-then-propagate variants read their inputs twice: 12 and 20 bytes per element)."""
@@ -130,6 +209,12 @@ def main() -> int:
                     help="give the backward its minimum workspace (the variant that forms S and dP in both passes) "
                          "instead of gfwa_backward_fast_workspace_bytes")
     ap.add_argument("--no-peak-probe", action="store_true", help="skip the pure-MFMA loop and the 1 GiB copy")
+    ap.add_argument("--power-pass-seconds", type=float, default=1.0,
+                    help="after the timed region: this many seconds of further steps while the board power and the shader "
+                         "clock are sampled from the driver's sysfs files (0: skip)")
+    ap.add_argument("--power-survey", action="store_true",
+                    help="the same sampling also for an idle device, the three MFMA loops, the forward alone and the "
+                         "backward alone (about 7 s more)")
     ap.add_argument("--one-pass-prefix", action="store_true",
                     help="always use gfwa_gate_prefix (one workgroup per row) for the prefix, also for few long rows")
     ap.add_argument("--cpu-heads", type=int, default=32)
@@ -295,6 +380,27 @@ def main() -> int:
 
     prof = g.gfwa_profile_read()
 
+    # ---- after the timed region: what the board draws while the same steps keep running
+    power = None
+    if args.power_pass_seconds > 0:
+        bp = BoardPower(torch)
+        power = bp.during(torch, step, args.power_pass_seconds)
+        if power is not None:
+            power["cap_w"] = bp.cap_watts()
+            power["how"] = (f"{args.power_pass_seconds:g} s of further steps after the timed region; hwmon power1_input and the "
+                            "active pp_dpm_sclk level sampled every 20 ms, the first 0.3 s dropped")
+            if args.power_survey:
+                sink = torch.zeros(1, dtype=torch.float32, device=dev)
+                secs = args.power_pass_seconds
+                survey = {"idle": bp.during(torch, lambda: time.sleep(0.005), secs)}
+                for mode, name in ((0, "mfma_constant_operands"), (1, "mfma_random_operands"), (2, "mfma_attention_mix")):
+                    survey[name] = bp.during(torch, lambda: g.gfwa_probe_mfma(sink, 2000, ncu, mode), secs)
+                survey["forward"] = bp.during(torch, lambda: fwd(Q, K, V, c, w, wl.scale, O=O, L=L), secs)
+                if wl.backward:
+                    survey["backward"] = bp.during(torch, lambda: bwd(Q, K, V, O, dO, c, L, w, wl.scale, workspace=ws, dQ=dQ,
+                                                                      dK=dK, dV=dV, dalpha=dalpha), secs)
+                power["survey"] = survey
+
     def stats(xs):
         xs = sorted(xs)
         return {"avg": round(sum(xs) / len(xs), 5), "median": round(xs[len(xs) // 2], 5), "min": round(xs[0], 5)}
@@ -372,6 +478,8 @@ def main() -> int:
                         "serves as run-in: the part needs about 25 steps to settle after a change of load; kernels.*: "
                         "the library's event pair around every launch in that pass (a few microseconds of overhead "
                         "each, visible on the ~10 us scans)")
+    if power is not None:
+        detail["power"] = power
     if achievable:
         detail["fwd_frac_of_achievable_mfma"] = round(f_fwd / fwd_ms / 1e9 / achievable["mfma_bf16_tflops"], 4)
         detail["fwd_frac_of_achievable_mfma_random_operands"] = round(
