@@ -218,7 +218,10 @@ int gfwa_version(void);
  * gate-gradient scan when the backward cuts few long rows into segments (its scan is then id 5);
  * gfwa_profile_kernel_name gives the same as text.
  * An event pair costs a few microseconds on the stream: kernels of about ten microseconds read
- * correspondingly longer than in a trace.  Not thread-safe; host memory only.
+ * correspondingly longer than in a trace.  The three calls may come from any host thread (the records
+ * are kept under a lock; the stop event of a launch is recorded by the thread that made it); a
+ * launch still in progress on another thread while gfwa_profile_read runs may be read before its
+ * stop event is recorded, so read after the launching threads are done.  Host memory only.
  */
 int gfwa_profile_enable(int on);
 int gfwa_profile_read(float *total_ms, int *launches, int n);

@@ -3,6 +3,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <atomic>
+#include <mutex>
 
 #include "../../include/gfwa.h"
 #include "gfwa_internal.h"
@@ -35,7 +37,8 @@ namespace {
 constexpr int kMaxRecords = 8192;
 struct ProfRecord { int kernel; hipEvent_t start, stop; };
 struct ProfState {
-    bool on = false;
+    std::atomic<bool> on{false};   // the only field read without the lock (every launch asks it)
+    std::mutex lock;               // slot allocation, reset and read-out may come from different host threads
     int used = 0;
     int created = 0;
     ProfRecord rec[kMaxRecords];
@@ -65,7 +68,9 @@ int device_cu_count() {
 }
 
 ProfScope::ProfScope(int kernel, hipStream_t s) : slot_(-1), s_(s) {
-    if (!g_prof.on || g_prof.used >= kMaxRecords) return;
+    if (!g_prof.on.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> hold(g_prof.lock);
+    if (g_prof.used >= kMaxRecords) return;
     const int i = g_prof.used;
     if (i >= g_prof.created) {
         if (hipEventCreate(&g_prof.rec[i].start) != hipSuccess) return;
@@ -270,8 +275,9 @@ int gfwa_probe_copy(const void* src, void* dst, size_t bytes, gfwa_stream_t stre
 }
 
 int gfwa_profile_enable(int on) {
-    g_prof.on = on != 0;
-    if (g_prof.on) g_prof.used = 0;  // records stay readable after profiling is switched off
+    std::lock_guard<std::mutex> hold(g_prof.lock);
+    g_prof.on.store(on != 0, std::memory_order_relaxed);
+    if (on) g_prof.used = 0;  // records stay readable after profiling is switched off
     return GFWA_OK;
 }
 
@@ -282,6 +288,7 @@ int gfwa_profile_read(float* total_ms, int* launches, int n) {
         total_ms[k] = 0.f;
         launches[k] = 0;
     }
+    std::lock_guard<std::mutex> hold(g_prof.lock);
     for (int i = 0; i < g_prof.used; ++i) {
         hipError_t e = hipEventSynchronize(g_prof.rec[i].stop);
         float ms = 0.f;
