@@ -28,7 +28,7 @@ class BoardPower:
     """Board power and shader clock of the GPU under test, read (never written) from the amdgpu driver's hwmon and
     pp_dpm_sclk files while a load runs.  None of it is needed for the timing; absent files just give no figures."""
 
-    def __init__(self, torch):
+    def __init__(self, torch, sysfs="/sys/class/drm"):
         import glob
         self.power = self.cap = self.sclk = None
         try:
@@ -36,7 +36,7 @@ class BoardPower:
             bus = f"{p.pci_domain_id:04x}:{p.pci_bus_id:02x}:{p.pci_device_id:02x}.0"
         except Exception:
             bus = ""
-        cards = sorted(glob.glob("/sys/class/drm/card[0-9]*/device"))
+        cards = sorted(glob.glob(os.path.join(sysfs, "card[0-9]*", "device")))
         mine = [c for c in cards if bus and os.path.realpath(c).lower().endswith(bus)] or (cards if len(cards) == 1 else [])
         for c in mine[:1]:
             for hw in sorted(glob.glob(os.path.join(c, "hwmon", "hwmon*"))):
