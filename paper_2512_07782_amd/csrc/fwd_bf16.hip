@@ -94,11 +94,22 @@ __global__ __launch_bounds__(kFwdThreads, kFwdResident<D>) void fwd_bf16_kernel(
 
     // Persistent workgroups: workgroup b takes the query tiles xcd_remap(b) + k * gridDim.x, so the
     // loads of the next tile are issued before the results of the current one are stored.
-    // (the slot inside a step is rotated from step to step so that the short tiles at the ends of a
-    // head do not always fall to the same workgroups)
+    // (the slot inside a round is rotated from round to round so that the short tiles at the ends of a
+    // head do not always fall to the same workgroups).  A last round with fewer tiles than workgroups is
+    // dealt out per XCD - every XCD an equal, contiguous share, taken by as many of its workgroups -
+    // instead of filling some XCDs and leaving the others without work; total_tiles stands for "none".
     const int wg_slot = xcd_remap(blockIdx.x, gridDim.x);
     int wg_step = 0;
-    auto tile_of = [&](int k) __attribute__((always_inline)) { return k * (int)gridDim.x + (wg_slot + 37 * k) % (int)gridDim.x; };
+    auto tile_of = [&](int k) __attribute__((always_inline)) {
+        constexpr int kXcd = 8;
+        const int G_ = (int)gridDim.x, base = k * G_, left = total_tiles - base;
+        if (left >= G_ || k == 0 || G_ % kXcd != 0) return base + (wg_slot + 37 * k) % G_;
+        if (left <= 0) return total_tiles;
+        const int per_xcd = G_ / kXcd, share = (left + kXcd - 1) / kXcd;
+        const int x = wg_slot / per_xcd, idx = (wg_slot % per_xcd + 37 * k) % per_xcd;
+        const int t = x * share + idx;
+        return (idx < share && t < left) ? base + t : total_tiles;
+    };
     int tile = tile_of(0);
     int bh, q0, qw0, t0, j_lo, j_hi, ntiles;
     size_t head_off;

@@ -560,6 +560,18 @@ def test_forward_backward_bf16_mid_size(g, oracle, ws_variant, B, H, N, d, w, he
     check_grads(got, ref, 1e-2, "mid")
 
 
+@pytest.mark.parametrize("B,H,N,d,w,heads", [
+    # more query tiles than resident workgroups (2 per CU at d = 128, 3 at d = 64, 256 CUs), not a multiple of them: the
+    # forward deals the tiles of its last round out per XCD; heads from the full first round and from that last one
+    (1, 20, 4099, 128, 300, [0, 15, 16, 19]), (1, 25, 4099, 64, 300, [0, 22, 23, 24]), (3, 11, 2100, 128, 77, [0, 30, 31, 32]),
+])
+def test_forward_bf16_partial_last_round(g, oracle, B, H, N, d, w, heads):
+    note("partial last round", B, H, N, d, w)
+    wl = gi.custom("plr", B, H, N, d, w, "bf16", alpha_mu=-1.5, index=15)
+    O, L, O_ref, L_ref = run_forward(g, oracle, wl, heads=heads)
+    check_bf16_forward(O, L, O_ref, L_ref, tag="partial last round")
+
+
 # ------------------------------------------------------------------------------------------
 # grouped-query layout
 # ------------------------------------------------------------------------------------------
