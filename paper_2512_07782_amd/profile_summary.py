@@ -4,22 +4,22 @@ The summaries of the training workload come from five profiler runs of the same 
 started from the repository root on the GPU machine (``cd /tmp && export TMPDIR=/tmp`` first; rocprofv3 of
 ROCm 7.2; counters are collected in runs of their own, without any trace option)::
 
-    rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- python3 bench.py --no-cpu-baseline
+    rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- python3 bench.py --no-cpu-baseline --power-pass-seconds 0
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT/fetch -- \\
-        python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --copy-calibration-mib 1024
+        python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0 --copy-calibration-mib 1024
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT/write -- \\
-        python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --copy-calibration-mib 1024
+        python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0 --copy-calibration-mib 1024
     rocprofv3 --pmc SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_WAIT_ANY \\
         SQ_VALU_MFMA_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS --output-format csv -d OUT/sqA -- \\
-        python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe
+        python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0
     rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_MFMA SQ_INSTS_LDS SQ_INSTS_SALU SQ_LDS_BANK_CONFLICT \\
         SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_ANY SQ_INSTS_VMEM --output-format csv -d OUT/sqB -- \\
-        python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe
+        python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0
 
 and then, with the standard output of the first run saved as OUT/kt.log::
 
     python3 -m paper_2512_07782_amd.profile_summary kernel-trace OUT/kt OUT/kt.log  > profiles/bench_long_bwd_kernel_trace.txt
-    (other workloads: the same trace with bench.py's arguments as a fourth argument, e.g. "--workload train_bwd --no-cpu-baseline")
+    (other workloads: the same trace with bench.py's arguments as a fourth argument, e.g. "--workload train_bwd --no-cpu-baseline --power-pass-seconds 0")
     python3 -m paper_2512_07782_amd.profile_summary hbm-traffic OUT/fetch OUT/write > profiles/hbm_traffic_long_bwd.txt
     python3 -m paper_2512_07782_amd.profile_summary sq-counters OUT/sqA OUT/sqB OUT/kt > profiles/sq_counters_long_bwd.txt
 
@@ -88,7 +88,7 @@ def bench_line(log: str) -> dict:
     return json.loads(lines[-1]), lines[-1].strip()
 
 
-def kernel_trace(kt_dir: str, log: str, bench_args: str = "--no-cpu-baseline") -> str:
+def kernel_trace(kt_dir: str, log: str, bench_args: str = "--no-cpu-baseline --power-pass-seconds 0") -> str:
     stats = one(os.path.join(kt_dir, "**", "*_kernel_stats.csv"))
     bj, raw = bench_line(log)
     out = [
@@ -152,9 +152,9 @@ def hbm_traffic(fetch_dir: str, write_dir: str) -> str:
         "# HBM traffic per launch of every kernel of bench.py, workload long_bwd (B=1 H=32 N=16384 d=128 w=1024",
         "# bf16), one MI355X, from two rocprofv3 counter runs (from the repository root, ROCm 7.2):",
         "#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT/fetch -- \\",
-        "#       python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --copy-calibration-mib 1024",
+        "#       python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0 --copy-calibration-mib 1024",
         "#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT/write -- \\",
-        "#       python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --copy-calibration-mib 1024",
+        "#       python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0 --copy-calibration-mib 1024",
         "# summary made by: python3 -m paper_2512_07782_amd.profile_summary hbm-traffic OUT/fetch OUT/write",
         "# The backward runs with the dS-block workspace (bench.py's default): the dK/dV kernel writes, and the dQ kernel",
         f"# reads, {spill / 1e6:.1f} MB of bf16 dS blocks per launch; both are counted in the algorithmic bytes below.",
@@ -206,10 +206,10 @@ def sq_counters(a_dir: str, b_dir: str, kt_dir: str) -> str:
         "root, ROCm 7.2):",
         "  rocprofv3 --pmc SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_WAIT_ANY SQ_VALU_MFMA_BUSY_CYCLES \\",
         "      SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS --output-format csv -d OUT/sqA -- \\",
-        "      python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe",
+        "      python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0",
         "  rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_MFMA SQ_INSTS_LDS SQ_INSTS_SALU SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE \\",
         "      SQ_ACTIVE_INST_ANY SQ_INSTS_VMEM --output-format csv -d OUT/sqB -- \\",
-        "      python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe",
+        "      python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-peak-probe --power-pass-seconds 0",
         "summary made by: python3 -m paper_2512_07782_amd.profile_summary sq-counters OUT/sqA OUT/sqB OUT/kt",
         f"Counter values are sums over the chip (256 CUs, 1024 SIMDs), averaged over the dispatches of each kernel (up to {n}).",
         "SQ_WAVE_CYCLES counts in units of four clock cycles, summed over the resident waves; these kernels keep two waves",
