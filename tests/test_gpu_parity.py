@@ -323,7 +323,11 @@ def test_forward_tiny_f32(g, oracle):
     assert rel_inf(L, L_ref) <= 1e-5
 
 
-@pytest.mark.parametrize("B,H,N,d,w", [(1, 2, 77, 64, 9), (2, 1, 130, 128, 500), (1, 1, 65, 128, 1)])
+# (the first three are served by the one-wave-per-row kernels, the others by the fp32 matrix-core kernels: the library
+# chooses by the size of the problem)
+@pytest.mark.parametrize("B,H,N,d,w", [(1, 2, 77, 64, 9), (2, 1, 130, 128, 500), (1, 1, 65, 128, 1),
+                                       (2, 3, 1500, 128, 700), (1, 4, 2100, 64, 300), (1, 4, 1237, 128, 5000),
+                                       (4, 16, 5001, 64, 1), (1, 8, 2049, 128, 33)])
 def test_forward_f32_ragged(g, oracle, B, H, N, d, w):
     note("forward f32 ragged", B, H, N, d, w)
     wl = gi.custom("f32r", B, H, N, d, w, "f32", alpha_mu=0.0, index=9)
@@ -485,7 +489,10 @@ def check_grads(got, ref, tol, tag="", tiny=False):
 
 
 @pytest.mark.parametrize("B,H,N,d,w", [(1, 2, 77, 64, 9), (2, 1, 130, 128, 500), (1, 1, 65, 128, 1),
-                                       (1, 1, 256, 64, 64)])
+                                       (1, 1, 256, 64, 64),
+                                       # large enough for the fp32 matrix-core kernels
+                                       (1, 4, 1100, 128, 400), (2, 2, 1000, 64, 300), (1, 3, 1237, 128, 3000),
+                                       (1, 8, 2049, 64, 33), (4, 16, 5001, 128, 1)])
 def test_backward_f32(g, oracle, B, H, N, d, w):
     note("backward f32", B, H, N, d, w)
     wl = gi.custom("bf32", B, H, N, d, w, "f32", alpha_mu=-1.0, index=11, backward=True)
@@ -611,7 +618,9 @@ def run_gqa(g, oracle, wl, groups=None):
     return got, ref
 
 
-@pytest.mark.parametrize("B,H,Hkv,N,d,w", [(1, 4, 2, 77, 64, 9), (2, 6, 2, 130, 128, 500), (1, 4, 1, 65, 64, 1)])
+@pytest.mark.parametrize("B,H,Hkv,N,d,w", [(1, 4, 2, 77, 64, 9), (2, 6, 2, 130, 128, 500), (1, 4, 1, 65, 64, 1),
+                                           # large enough for the fp32 matrix-core kernels
+                                           (1, 8, 2, 1100, 128, 400), (1, 4, 1, 1300, 64, 200)])
 def test_gqa_f32(g, oracle, B, H, Hkv, N, d, w):
     note("gqa f32", B, H, Hkv, N, d, w)
     wl = gi.custom("gqa32", B, H, N, d, w, "f32", alpha_mu=-1.0, index=13, backward=True, kv_heads=Hkv)
