@@ -120,6 +120,8 @@ WORKLOADS: Dict[str, Workload] = {
         # grouped-query variants, 4 query heads per key/value head as in the paper's training tables
         Workload("lm_gqa_bwd", 6, 4, 16, 4096, 64, 512, "bf16", alpha_mu=-2.0, backward=True, kv_heads=4),
         Workload("long_gqa_bwd", 7, 1, 32, 16384, 128, 1024, "bf16", alpha_mu=-3.0, backward=True, kv_heads=8),
+        # fp32 storage at a size that fills the chip (the fp32 matrix-core kernels)
+        Workload("mid_bwd_f32", 8, 2, 16, 4096, 128, 1024, "f32", alpha_mu=-2.0, backward=True),
     ]
 }
 
