@@ -52,6 +52,11 @@ LIB = {
     "bwd_dq_bf16_kernel<64>": "bwd_dq",
     "bwd_dkv8_bf16_kernel<128, false>": "bwd_dkv",
     "bwd_dq_bf16_kernel<128>": "bwd_dq",
+    # fp32 storage
+    "fwd_f32_mfma_kernel<128>": "forward", "fwd_f32_mfma_kernel<64>": "forward", "fwd_f32_kernel": "forward",
+    "rowdot_f32_kernel": "bwd_rowdot",
+    "bwd_dkv_f32_mfma_kernel<128>": "bwd_dkv", "bwd_dkv_f32_mfma_kernel<64>": "bwd_dkv", "bwd_dkv_f32_kernel": "bwd_dkv",
+    "bwd_dq_f32_mfma_kernel<128>": "bwd_dq", "bwd_dq_f32_mfma_kernel<64>": "bwd_dq", "bwd_dq_f32_kernel": "bwd_dq",
 }
 # the long_bwd workload of bench.py
 B, H, N, D, W = 1, 32, 16384, 128, 1024
