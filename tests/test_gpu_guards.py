@@ -49,7 +49,7 @@ def dev(x, dtype):
 
 SHAPES = [  # B, H, Hkv, N, d, w: ragged in every tile size the kernels use
     (1, 2, 2, 333, 128, 50), (2, 4, 2, 77, 64, 200), (1, 1, 1, 1, 128, 1), (1, 3, 1, 1027, 128, 1024),
-    (1, 2, 1, 259, 64, 64),
+    (1, 2, 1, 259, 64, 64), (2, 4, 2, 1301, 64, 300),   # (the last and the fourth: large enough for the fp32 matrix-core kernels)
 ]
 
 
