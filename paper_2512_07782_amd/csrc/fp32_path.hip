@@ -207,10 +207,14 @@ __global__ __launch_bounds__(kF32Threads, 2) void fwd_f32_mfma_kernel(
         }
         lh = fmaf(lh, a, psum);
         mrun = mnew;
+        if (__builtin_amdgcn_ballot_w64(a != 1.0f) != 0) {  // the maximum of some row has moved (rare after the first blocks)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] *= a;
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= a;
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db] = mfma_f32(Vs[f32_tile_off<D>(acc_row(v, h), 32 * db + lq)], s[v], o[db]);
         }
