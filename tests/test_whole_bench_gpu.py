@@ -20,10 +20,10 @@ def _run(monkeypatch, capsys, *argv):
     return json.loads(lines[0])
 
 
-def _check_common(d, steps, warmup):
+def _check_common(d, steps, warmup, dtype="bf16"):
     assert d["n_gpus"] == 1 and d["steps"] == steps and d["warmup"] == warmup
     assert d["higher_is_better"] is True and d["scaling"] == "weak" and d["data"] == "synthetic"
-    assert d["unit"] == "TFLOP/s" and d["dtype"] == "bf16" and d["vs_baseline"] is None
+    assert d["unit"] == "TFLOP/s" and d["dtype"] == dtype and d["vs_baseline"] is None
     assert isinstance(d["config"]["workload"], str) and "model" not in d["config"]
     assert d["value"] > 0 and d["ms_per_step"] > 0
     r = d["roofline"]
@@ -60,3 +60,13 @@ def test_default_workload_short(monkeypatch, capsys):
     k = d["kernels"]
     for name in ("forward", "bwd_rowdot", "bwd_dkv", "bwd_dq"):
         assert k[name]["launches"] == 3 and k[name]["avg_ms"] > 0
+
+
+def test_fp32_workload_is_priced_against_the_fp32_peak(monkeypatch, capsys):
+    d = _run(monkeypatch, capsys, "--workload", "mid_bwd_f32", "--steps", "2", "--warmup", "1", "--no-peak-probe",
+             "--power-pass-seconds", "0", "--cpu-heads", "2")
+    _check_common(d, 2, 1, dtype="f32")
+    assert d["roofline"]["bound"] == "mfma" and d["roofline"]["peak"] == 157.3
+    assert 0 < d["detail"]["fwd_frac_f32_peak"] < 1 and 0 < d["detail"]["bwd_frac_f32_peak"] < 1
+    par = d["detail"]["parity"]
+    assert par["within_stated_tolerances"] is True and par["O_rel_inf"] <= par["fp32_bar"] < 1e-3
